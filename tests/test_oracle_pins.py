@@ -1,0 +1,470 @@
+"""Pins for the fp64 oracle: closed forms, invariants, brute force, finite differences and an
+independent stock-PyTorch fp64 autograd implementation.  None of these need a GPU."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder_layer as dl
+from oracle import lm_stack as lm
+from synth import inputs as si
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _cfg(B=1, S=16, D=16, Hq=4, Hkv=2, dh=4, F=24, base=10000.0, layout=0):
+    return si.LayerConfig(B, S, D, Hq, Hkv, dh, F, 1e-5, base, layout)
+
+
+def _rand_layer(cfg, seed=1, w_std=0.3):
+    inp = si.to_f64(si.make_layer_inputs(cfg, seed=seed, w_std=w_std))
+    x, dy = inp.pop("x"), inp.pop("dy")
+    return x, dy, inp
+
+
+# ------------------------------------------------------------------ value printed by the paper
+def test_block_param_count_matches_paper_message_size():
+    vals = {}
+    for line in open(os.path.join(GOLDEN, "block_message_size.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            vals[k] = float(v)
+    n = si.layer_param_count(si.CONFIGS["8b"])
+    assert n == int(vals["block_params"]) == 218112000
+    msg_mb = n * vals["bytes_per_param"] / vals["dp_degree"] / 1e6
+    assert abs(msg_mb - vals["message_megabytes_approx"]) < 0.05  # 0.426 MB ~ "approx. 0.4 MB"
+
+
+# ------------------------------------------------------------------ softmax / causality
+def test_softmax_rows_sum_to_one_and_are_causal():
+    rng = np.random.default_rng(0)
+    q, k = rng.standard_normal((12, 8)) * 3, rng.standard_normal((12, 8)) * 3
+    p, lse = dl._causal_probs(q, k)
+    assert np.abs(p.sum(-1) - 1).max() < 1e-12
+    assert np.all(np.triu(p, 1) == 0)
+    assert p[0, 0] == 1.0
+    # lse is the log of the un-normalised row sum
+    s = q @ k.T / math.sqrt(8)
+    for i in range(12):
+        assert abs(lse[i] - math.log(sum(math.exp(s[i, j]) for j in range(i + 1)))) < 1e-12
+
+
+def test_layer_is_causal():
+    cfg = _cfg(B=2, S=16)
+    x, dy, w = _rand_layer(cfg)
+    y = dl.layer_forward(cfg, x, w)["y"]
+    t = 9
+    x2 = x.copy()
+    x2[:, t + 1:] += np.random.default_rng(3).standard_normal(x2[:, t + 1:].shape)
+    y2 = dl.layer_forward(cfg, x2, w)["y"]
+    assert np.abs(y[:, :t + 1] - y2[:, :t + 1]).max() <= 1e-12
+    assert np.abs(y[:, t + 1:] - y2[:, t + 1:]).max() > 1e-3
+
+
+def test_attention_first_row_is_v0_and_zero_q_gives_prefix_mean():
+    rng = np.random.default_rng(1)
+    B, S, Hq, Hkv, dh = 2, 10, 4, 2, 6
+    q = rng.standard_normal((B, S, Hq, dh))
+    k = rng.standard_normal((B, S, Hkv, dh))
+    v = rng.standard_normal((B, S, Hkv, dh))
+    o, _ = dl.attention_fwd(q, k, v)
+    for h in range(Hq):
+        assert np.abs(o[:, 0, h] - v[:, 0, h // 2]).max() < 1e-14
+    o0, lse0 = dl.attention_fwd(np.zeros_like(q), k, v)
+    prefix_mean = np.cumsum(v, axis=1) / np.arange(1, S + 1)[None, :, None, None]
+    for h in range(Hq):
+        assert np.abs(o0[:, :, h] - prefix_mean[:, :, h // 2]).max() < 1e-13
+        assert np.abs(lse0[:, h] - np.log(np.arange(1, S + 1))).max() < 1e-13
+
+
+def _attention_brute(q, k, v):
+    """Scalar triple loop straight from the definition."""
+    B, S, Hq, dh = q.shape
+    G = Hq // k.shape[2]
+    o = np.zeros_like(q)
+    for b in range(B):
+        for h in range(Hq):
+            j = h // G
+            for i in range(S):
+                sc = [sum(q[b, i, h, d] * k[b, t, j, d] for d in range(dh)) / math.sqrt(dh)
+                      for t in range(i + 1)]
+                mx = max(sc)
+                e = [math.exp(s - mx) for s in sc]
+                z = sum(e)
+                for d in range(dh):
+                    o[b, i, h, d] = sum(e[t] / z * v[b, t, j, d] for t in range(i + 1))
+    return o
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (4, 2), (4, 1)])
+def test_attention_matches_brute_force(Hq, Hkv):
+    rng = np.random.default_rng(2)
+    B, S, dh = 2, 9, 4
+    q = rng.standard_normal((B, S, Hq, dh)) * 2
+    k = rng.standard_normal((B, S, Hkv, dh)) * 2
+    v = rng.standard_normal((B, S, Hkv, dh))
+    o, _ = dl.attention_fwd(q, k, v)
+    assert np.abs(o - _attention_brute(q, k, v)).max() < 1e-13
+
+
+def test_gqa_equals_mha_with_repeated_kv_and_grads_sum_over_group():
+    rng = np.random.default_rng(4)
+    B, S, Hq, Hkv, dh = 1, 8, 4, 2, 4
+    G = Hq // Hkv
+    q = rng.standard_normal((B, S, Hq, dh))
+    k = rng.standard_normal((B, S, Hkv, dh))
+    v = rng.standard_normal((B, S, Hkv, dh))
+    do = rng.standard_normal((B, S, Hq, dh))
+    kr, vr = np.repeat(k, G, axis=2), np.repeat(v, G, axis=2)
+    o, _ = dl.attention_fwd(q, k, v)
+    o_m, _ = dl.attention_fwd(q, kr, vr)
+    assert np.abs(o - o_m).max() < 1e-14
+    dq, dk, dv = dl.attention_bwd(q, k, v, do)
+    dq_m, dk_m, dv_m = dl.attention_bwd(q, kr, vr, do)
+    assert np.abs(dq - dq_m).max() < 1e-13
+    assert np.abs(dk - dk_m.reshape(B, S, Hkv, G, dh).sum(3)).max() < 1e-13
+    assert np.abs(dv - dv_m.reshape(B, S, Hkv, G, dh).sum(3)).max() < 1e-13
+
+
+def test_attention_bwd_finite_differences():
+    rng = np.random.default_rng(5)
+    B, S, Hq, Hkv, dh = 1, 7, 4, 2, 4
+    q = rng.standard_normal((B, S, Hq, dh))
+    k = rng.standard_normal((B, S, Hkv, dh))
+    v = rng.standard_normal((B, S, Hkv, dh))
+    do = rng.standard_normal((B, S, Hq, dh))
+    dq, dk, dv = dl.attention_bwd(q, k, v, do)
+    L = lambda q_, k_, v_: np.sum(dl.attention_fwd(q_, k_, v_)[0] * do)
+    h = 1e-6
+    for name, g in (("q", dq), ("k", dk), ("v", dv)):
+        u = rng.standard_normal(g.shape)
+        args_p = {"q": q, "k": k, "v": v}
+        args_m = dict(args_p)
+        args_p = dict(args_p)
+        args_p[name] = args_p[name] + h * u
+        args_m[name] = args_m[name] - h * u
+        fd = (L(args_p["q"], args_p["k"], args_p["v"]) - L(args_m["q"], args_m["k"], args_m["v"])) / (2 * h)
+        an = np.sum(g * u)
+        assert abs(fd - an) <= 1e-7 * max(1.0, abs(an)), name
+
+
+# ------------------------------------------------------------------ RoPE
+@pytest.mark.parametrize("layout", [0, 1])
+def test_rope_properties(layout):
+    rng = np.random.default_rng(6)
+    S, dh = 20, 8
+    phi = dl.rope_angles(S, dh, 10000.0)
+    # angle table: phi[p, i] = p * base^(-2i/dh)
+    assert phi[0].max() == 0 and abs(phi[7, 0] - 7.0) < 1e-15
+    assert abs(phi[3, 2] - 3 * 10000.0 ** (-4 / 8)) < 1e-15
+    z = rng.standard_normal((2, S, 3, dh))
+    r = dl.rope_rotate(z, phi, layout)
+    assert np.array_equal(r[:, 0], z[:, 0])                          # position 0 is the identity
+    assert np.abs(np.linalg.norm(r, axis=-1) - np.linalg.norm(z, axis=-1)).max() < 1e-13
+    back = dl.rope_rotate(r, phi, layout, inverse=True)
+    assert np.abs(back - z).max() < 1e-13                            # rotation by -phi undoes it
+    # <rope(q, m), rope(k, n)> depends only on m - n
+    qv, kv = rng.standard_normal(dh), rng.standard_normal(dh)
+    qs = dl.rope_rotate(np.broadcast_to(qv, (1, S, 1, dh)).copy(), phi, layout)[0, :, 0]
+    ks = dl.rope_rotate(np.broadcast_to(kv, (1, S, 1, dh)).copy(), phi, layout)[0, :, 0]
+    gram = qs @ ks.T
+    for d in (0, 3, 7):
+        diag = np.array([gram[m, m - d] for m in range(d, S)])
+        assert np.abs(diag - diag[0]).max() < 1e-12
+    # explicit 2x2 rotation of one pair at one position
+    p, i = 5, 1
+    ia, ib = (i, i + dh // 2) if layout == 0 else (2 * i, 2 * i + 1)
+    a, b = z[1, p, 2, ia], z[1, p, 2, ib]
+    ang = p * 10000.0 ** (-2 * i / dh)
+    assert abs(r[1, p, 2, ia] - (a * math.cos(ang) - b * math.sin(ang))) < 1e-14
+    assert abs(r[1, p, 2, ib] - (a * math.sin(ang) + b * math.cos(ang))) < 1e-14
+
+
+def test_rope_layouts_coincide_under_row_permutation():
+    """Half-split RoPE with weights Wq, Wk equals interleaved RoPE with the rows of each head
+    of Wq, Wk permuted (2i <- i, 2i+1 <- i + dh/2): attention output is identical."""
+    cfg0 = _cfg(layout=0)
+    cfg1 = _cfg(layout=1)
+    x, dy, w = _rand_layer(cfg0)
+    dh = cfg0.head_dim
+    perm = np.empty(dh, dtype=int)
+    perm[0::2] = np.arange(dh // 2)
+    perm[1::2] = np.arange(dh // 2) + dh // 2
+    w1 = dict(w)
+    for name, H in (("wq", cfg0.n_q_heads), ("wk", cfg0.n_kv_heads)):
+        w1[name] = w[name].reshape(H, dh, -1)[:, perm].reshape(w[name].shape)
+    y0 = dl.layer_forward(cfg0, x, w)["y"]
+    y1 = dl.layer_forward(cfg1, x, w1)["y"]
+    assert np.abs(y0 - y1).max() < 1e-12
+
+
+# ------------------------------------------------------------------ RMSNorm
+def test_rmsnorm_closed_forms():
+    D, eps = 16, 1e-5
+    gamma = np.linspace(0.5, 1.5, D)
+    c = 3.0
+    h, rstd = dl.rmsnorm_fwd(np.full((2, D), c), gamma, eps)
+    assert np.abs(h - gamma * c / math.sqrt(c * c + eps)).max() < 1e-14
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((5, D))
+    h1, _ = dl.rmsnorm_fwd(x, gamma, 0.0)
+    h2, _ = dl.rmsnorm_fwd(1e3 * x, gamma, 0.0)
+    assert np.abs(h1 - h2).max() < 1e-12                             # scale invariance at eps = 0
+    assert np.abs(np.mean((h1 / gamma) ** 2, -1) - 1).max() < 1e-12  # unit mean square
+    # <dx, x> = eps * rstd^3 * <dxhat, x> per token
+    dh = rng.standard_normal((5, D))
+    h, rstd = dl.rmsnorm_fwd(x, gamma, eps)
+    dx, dg = dl.rmsnorm_bwd(x, gamma, rstd, dh)
+    lhs = np.sum(dx * x, -1)
+    rhs = eps * rstd ** 3 * np.sum(dh * gamma * x, -1)
+    assert np.abs(lhs - rhs).max() < 1e-12
+    # finite differences
+    u, ug = rng.standard_normal(x.shape), rng.standard_normal(D)
+    L = lambda x_, g_: np.sum(dl.rmsnorm_fwd(x_, g_, eps)[0] * dh)
+    e = 1e-6
+    assert abs((L(x + e * u, gamma) - L(x - e * u, gamma)) / (2 * e) - np.sum(dx * u)) < 1e-7
+    assert abs((L(x, gamma + e * ug) - L(x, gamma - e * ug)) / (2 * e) - np.sum(dg * ug)) < 1e-7
+
+
+# ------------------------------------------------------------------ SwiGLU
+def test_swiglu_closed_forms():
+    assert dl.swiglu_fwd(np.array([0.0]), np.array([5.0]))[0] == 0.0
+    dg, du = dl.swiglu_bwd(np.array([0.0]), np.array([1.0]), np.array([1.0]))
+    assert dg[0] == 0.5 and du[0] == 0.0                              # silu'(0) = 1/2, silu(0) = 0
+    g, u = np.array([40.0]), np.array([-2.0])
+    assert abs(dl.swiglu_fwd(g, u)[0] - g[0] * u[0]) < 1e-12           # g -> +inf: silu(g) -> g
+    assert abs(dl.swiglu_fwd(-g, u)[0]) < 1e-12                        # g -> -inf: silu(g) -> 0
+    assert abs(dl.swiglu_fwd(np.array([1.0]), np.array([1.0]))[0] - 1 / (1 + math.exp(-1))) < 1e-15
+    rng = np.random.default_rng(8)
+    g, u, da = rng.standard_normal(50) * 3, rng.standard_normal(50), rng.standard_normal(50)
+    dg, du = dl.swiglu_bwd(g, u, da)
+    e = 1e-6
+    fd_g = (dl.swiglu_fwd(g + e, u) - dl.swiglu_fwd(g - e, u)) / (2 * e) * da
+    fd_u = (dl.swiglu_fwd(g, u + e) - dl.swiglu_fwd(g, u - e)) / (2 * e) * da
+    assert np.abs(fd_g - dg).max() < 1e-8 and np.abs(fd_u - du).max() < 1e-8
+
+
+# ------------------------------------------------------------------ cross-entropy
+def test_ce_closed_forms():
+    T, V = 6, si.VOCAB_8B
+    tg = np.arange(T) * 1000
+    loss, dlg, lse = lm.ce_loss_fwd_bwd(np.zeros((T, V)), tg)
+    assert abs(loss - 11.7617835456) < 1e-9 and abs(loss - math.log(V)) < 1e-12
+    assert np.abs(dlg.sum(-1)).max() < 1e-15
+    assert abs(dlg[2, tg[2]] - (1.0 / V - 1.0) / T) < 1e-18
+    rng = np.random.default_rng(9)
+    T, V = 7, 33
+    lg = rng.standard_normal((T, V)) * 4
+    tg = rng.integers(0, V, T)
+    loss, dlg, _ = lm.ce_loss_fwd_bwd(lg, tg)
+    loss2, dlg2, _ = lm.ce_loss_fwd_bwd(lg + rng.standard_normal((T, 1)) * 10, tg)
+    assert abs(loss - loss2) < 1e-12 and np.abs(dlg - dlg2).max() < 1e-14   # shift invariance
+    assert np.abs(dlg.sum(-1)).max() < 1e-15
+    # definition, scalar loops
+    ref = 0.0
+    for t in range(T):
+        ref += math.log(sum(math.exp(lg[t, j]) for j in range(V))) - lg[t, tg[t]]
+    assert abs(loss - ref / T) < 1e-12
+    p = np.exp(lg[3]) / np.exp(lg[3]).sum()
+    assert abs(dlg[3, tg[3]] - (p[tg[3]] - 1) / T) < 1e-15
+    u = rng.standard_normal(lg.shape)
+    e = 1e-6
+    fd = (lm.ce_loss_fwd_bwd(lg + e * u, tg)[0] - lm.ce_loss_fwd_bwd(lg - e * u, tg)[0]) / (2 * e)
+    assert abs(fd - np.sum(dlg * u)) < 1e-8
+    # grad_scale multiplies the gradient only
+    l3, d3, _ = lm.ce_loss_fwd_bwd(lg, tg, grad_scale=2.5)
+    assert l3 == loss and np.abs(d3 - 2.5 * dlg).max() < 1e-15
+
+
+def test_embedding_scatter_add():
+    rng = np.random.default_rng(10)
+    V, D = 11, 3
+    ids = np.array([[1, 4, 1, 1], [4, 0, 10, 1]])
+    E = rng.standard_normal((V, D))
+    assert np.array_equal(lm.embed_fwd(E, ids)[1, 2], E[10])
+    dx = rng.standard_normal((2, 4, D))
+    dE = lm.embed_bwd(dx, ids, V)
+    assert np.abs(dE[1] - (dx[0, 0] + dx[0, 2] + dx[0, 3] + dx[1, 3])).max() < 1e-15
+    assert np.abs(dE[4] - (dx[0, 1] + dx[1, 0])).max() < 1e-15
+    assert np.all(dE[[2, 3, 5, 6, 7, 8, 9]] == 0)
+
+
+# ------------------------------------------------------------------ whole layer: finite differences
+@pytest.mark.parametrize("layout", [0, 1])
+def test_layer_backward_finite_differences(layout):
+    cfg = _cfg(B=2, S=8, D=16, Hq=4, Hkv=2, dh=4, F=24, layout=layout)
+    x, dy, w = _rand_layer(cfg, seed=11)
+    f = dl.layer_forward(cfg, x, w)
+    r = dl.layer_backward(cfg, x, w, dy, f)
+    rng = np.random.default_rng(12)
+    h = 1e-5
+
+    def L(x_, w_):
+        return np.sum(dl.layer_forward(cfg, x_, w_)["y"] * dy)
+
+    u = rng.standard_normal(x.shape)
+    fd = (L(x + h * u, w) - L(x - h * u, w)) / (2 * h)
+    an = np.sum(r["dx"] * u)
+    assert abs(fd - an) <= 1e-6 * max(1.0, abs(an))
+    for name in si.WEIGHT_NAMES:
+        u = rng.standard_normal(w[name].shape)
+        wp, wm = dict(w), dict(w)
+        wp[name] = w[name] + h * u
+        wm[name] = w[name] - h * u
+        fd = (L(x, wp) - L(x, wm)) / (2 * h)
+        an = np.sum(r[name] * u)
+        assert abs(fd - an) <= 1e-6 * max(1.0, abs(an)), name
+
+
+# ------------------------------------------------------------------ independent PyTorch fp64 autograd
+def _torch_layer(cfg, x, w):
+    F = torch.nn.functional
+    B, S, D = x.shape
+    Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+
+    def norm(t, g):
+        return t * torch.rsqrt(t.pow(2).mean(-1, keepdim=True) + cfg.rms_eps) * g
+
+    def rope(z):
+        half = dh // 2
+        inv = 1.0 / (cfg.rope_base ** (torch.arange(0, dh, 2, dtype=torch.float64) / dh))
+        ang = torch.outer(torch.arange(S, dtype=torch.float64), inv)
+        cos, sin = ang.cos()[None, :, None, :], ang.sin()[None, :, None, :]
+        if cfg.rope_layout == 0:
+            a, b = z[..., :half], z[..., half:]
+            return torch.cat([a * cos - b * sin, a * sin + b * cos], -1)
+        zc = torch.view_as_complex(z.reshape(*z.shape[:-1], half, 2).contiguous())
+        rot = torch.polar(torch.ones_like(ang), ang)[None, :, None, :]
+        return torch.view_as_real(zc * rot).reshape(z.shape)
+
+    h1 = norm(x, w["g_attn"])
+    q = rope(F.linear(h1, w["wq"]).view(B, S, Hq, dh)).transpose(1, 2)
+    k = rope(F.linear(h1, w["wk"]).view(B, S, Hkv, dh)).transpose(1, 2)
+    v = F.linear(h1, w["wv"]).view(B, S, Hkv, dh).transpose(1, 2)
+    k = k.repeat_interleave(Hq // Hkv, dim=1)
+    v = v.repeat_interleave(Hq // Hkv, dim=1)
+    sc = q @ k.transpose(-1, -2) / math.sqrt(dh)
+    sc = sc.masked_fill(~torch.ones(S, S, dtype=torch.bool).tril(), float("-inf"))
+    o = (torch.softmax(sc, -1) @ v).transpose(1, 2).reshape(B, S, Hq * dh)
+    y1 = x + F.linear(o, w["wo"])
+    h2 = norm(y1, w["g_mlp"])
+    return y1 + F.linear(F.silu(F.linear(h2, w["w_gate"])) * F.linear(h2, w["w_up"]), w["w_down"])
+
+
+@pytest.mark.parametrize("cfg", [
+    si.CONFIGS["tiny"],
+    si.LayerConfig(2, 24, 32, 4, 2, 8, 40, 1e-5, 500000.0, 0),
+    si.LayerConfig(2, 24, 32, 4, 1, 8, 40, 1e-5, 10000.0, 1),
+])
+def test_layer_matches_torch_fp64_autograd(cfg):
+    x, dy, w = _rand_layer(cfg, seed=0, w_std=0.02 if cfg.d_model >= 128 else 0.3)
+    f = dl.layer_forward(cfg, x, w)
+    r = dl.layer_backward(cfg, x, w, dy, f)
+    xt = torch.tensor(x, requires_grad=True)
+    wt = {k: torch.tensor(v, requires_grad=True) for k, v in w.items()}
+    yt = _torch_layer(cfg, xt, wt)
+    yt.backward(torch.tensor(dy))
+    assert np.abs(f["y"] - yt.detach().numpy()).max() < 1e-10
+    assert np.abs(r["dx"] - xt.grad.numpy()).max() < 1e-10
+    for name in si.WEIGHT_NAMES:
+        ref = wt[name].grad.numpy()
+        assert np.abs(r[name] - ref).max() < 1e-10 * max(1.0, np.abs(ref).max()), name
+
+
+# ------------------------------------------------------------------ stack: FD + torch cross-check
+def _tiny_stack(L=2, V=53, seed=13):
+    cfg = _cfg(B=2, S=8, D=16, Hq=4, Hkv=2, dh=4, F=24)
+    raw = si.make_stack_inputs(cfg, L, V, seed=seed)
+    s = si.to_f64(raw)
+    # larger weights than the production init so that every term of the gradient matters
+    s["embed"] = s["embed"] * 40
+    s["w_lm"] = s["w_lm"] * 20
+    for w in s["layers"]:
+        for k_ in w:
+            if not k_.startswith("g_"):
+                w[k_] = w[k_] * 12
+    return cfg, s
+
+
+def test_stack_backward_finite_differences():
+    cfg, s = _tiny_stack()
+    args = (cfg, s["ids"], s["targets"], s["embed"], s["layers"], s["g_final"], s["w_lm"])
+    st = lm.stack_forward(*args, row_chunk=5)
+    g = lm.stack_backward(*args, st, row_chunk=5)
+    rng = np.random.default_rng(14)
+    h = 1e-5
+
+    def loss(embed=s["embed"], layers=s["layers"], g_final=s["g_final"], w_lm=s["w_lm"]):
+        return lm.stack_forward(cfg, s["ids"], s["targets"], embed, layers, g_final, w_lm)["loss"]
+
+    for name, grad, kw in (("embed", g["embed"], "embed"), ("w_lm", g["w_lm"], "w_lm"),
+                           ("g_final", g["g_final"], "g_final")):
+        u = rng.standard_normal(grad.shape)
+        fd = (loss(**{kw: s[name] + h * u}) - loss(**{kw: s[name] - h * u})) / (2 * h)
+        an = np.sum(grad * u)
+        assert abs(fd - an) <= 1e-6 * max(1e-3, abs(an)), name
+    for l in range(len(s["layers"])):
+        for name in ("wq", "w_down", "g_mlp"):
+            u = rng.standard_normal(s["layers"][l][name].shape)
+            lp = [dict(w) for w in s["layers"]]
+            lmn = [dict(w) for w in s["layers"]]
+            lp[l][name] = lp[l][name] + h * u
+            lmn[l][name] = lmn[l][name] - h * u
+            fd = (loss(layers=lp) - loss(layers=lmn)) / (2 * h)
+            an = np.sum(g["layers"][l][name] * u)
+            assert abs(fd - an) <= 1e-6 * max(1e-3, abs(an)), (l, name)
+    # dX0 is the gradient w.r.t. the gathered embeddings; scatter-add gives dE
+    assert np.abs(lm.embed_bwd(g["dx0"], s["ids"], s["embed"].shape[0]) - g["embed"]).max() == 0
+
+
+def test_stack_matches_torch_fp64_autograd():
+    cfg, s = _tiny_stack(L=2, V=37, seed=15)
+    args = (cfg, s["ids"], s["targets"], s["embed"], s["layers"], s["g_final"], s["w_lm"])
+    st = lm.stack_forward(*args, row_chunk=7)
+    g = lm.stack_backward(*args, st, row_chunk=7)
+    E = torch.tensor(s["embed"], requires_grad=True)
+    layers = [{k: torch.tensor(v, requires_grad=True) for k, v in w.items()} for w in s["layers"]]
+    gf = torch.tensor(s["g_final"], requires_grad=True)
+    wl = torch.tensor(s["w_lm"], requires_grad=True)
+    x = torch.nn.functional.embedding(torch.tensor(s["ids"]), E)
+    x.retain_grad()
+    h = x
+    for w in layers:
+        h = _torch_layer(cfg, h, w)
+    hf = h * torch.rsqrt(h.pow(2).mean(-1, keepdim=True) + cfg.rms_eps) * gf
+    logits = torch.nn.functional.linear(hf, wl)
+    loss = torch.nn.functional.cross_entropy(logits.view(-1, wl.shape[0]),
+                                             torch.tensor(s["targets"]).view(-1))
+    loss.backward()
+    assert abs(st["loss"] - loss.item()) < 1e-12
+    assert np.abs(g["dx0"] - x.grad.numpy()).max() < 1e-12
+    assert np.abs(g["embed"] - E.grad.numpy()).max() < 1e-12
+    assert np.abs(g["w_lm"] - wl.grad.numpy()).max() < 1e-12
+    assert np.abs(g["g_final"] - gf.grad.numpy()).max() < 1e-12
+    for l, w in enumerate(layers):
+        for name in si.WEIGHT_NAMES:
+            assert np.abs(g["layers"][l][name] - w[name].grad.numpy()).max() < 1e-11, (l, name)
+
+
+# ------------------------------------------------------------------ input generator
+def test_bf16_rounding_is_nearest_even():
+    f = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -7, -1.0 - 2 ** -8 - 2 ** -20],
+                 dtype=np.float32)
+    b = si.bf16_bits_to_f32(si.f32_to_bf16_bits(f))
+    assert list(b) == [1.0, 1.0, 1.0 + 2 ** -6, 1.0 + 2 ** -7, -1.0 - 2 ** -7]
+    t = torch.tensor(np.random.default_rng(0).standard_normal(4096).astype(np.float32))
+    ours = si.f32_to_bf16_bits(t.numpy())
+    theirs = t.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(ours, theirs)
+
+
+def test_inputs_are_seeded_and_distributed_as_stated():
+    cfg = si.CONFIGS["tiny"]
+    a, b = si.make_layer_inputs(cfg, seed=0), si.make_layer_inputs(cfg, seed=0)
+    assert all(np.array_equal(a[k], b[k]) for k in a)
+    v = si.to_f64(a)
+    assert abs(v["x"].std() - 1) < 0.05 and abs(v["wq"].std() - 0.02) < 0.002
+    assert abs(v["g_attn"].mean() - 1) < 0.01
+    assert si.layer_fwd_bwd_flops(si.CONFIGS["8b"]) == pytest.approx(24739.0e9, rel=1e-4)
