@@ -1,0 +1,190 @@
+/*
+ * dlayer.h - C ABI of the MI355X (gfx950) decoder-layer training-step library.
+ *
+ * The library computes one bf16 training step (forward + backward) of the model the paper
+ * benchmarks (Fig. 2: an 8B Llama-3-style decoder stack; the "transformer block" of its
+ * Training Pipeline paragraph): pre-norm RMSNorm, Q/K/V projections, rotary position
+ * embedding, causal softmax attention with grouped KV heads, output projection with residual,
+ * and a SwiGLU MLP with residual; plus token embedding, final norm, LM head and mean softmax
+ * cross-entropy (the training loss of Fig. 2a).  The paper gives no equations; the definitions
+ * are the standard ones and are restated at each entry point.
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, 16-byte aligned, dense
+ *     row-major.  bf16 = upper 16 bits of an IEEE fp32 (1-8-7).  "f32" = IEEE fp32.
+ *   - Activations are [T, features] with T = batch * seq tokens (equivalently [B, S, features]);
+ *     head tensors are [T, H, head_dim] (the projection output viewed as heads, no transpose);
+ *     weights are [out_features, in_features] (y = x W^T); norm gains are [D].
+ *   - Contractions take bf16 operands and accumulate in fp32; reductions (norm statistics,
+ *     softmax, gain gradients, loss) are fp32; stored results are bf16 unless stated.
+ *   - The library never allocates, frees or keeps device memory.  Scratch is passed in by the
+ *     caller (`workspace`, sized by the matching *_workspace_bytes query; contents are
+ *     undefined on entry and on return and may be reused by the next call on the same stream).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work on it and return without synchronising; outputs are valid once the stream has been
+ *     synchronised by the caller.
+ *   - Return value: 0 on success; DLAYER_ERR_INVALID for a rejected argument (null or
+ *     misaligned pointer, unsupported shape) - nothing has been launched and outputs are
+ *     untouched; DLAYER_ERR_DEVICE if the current device is not gfx950; DLAYER_ERR_LAUNCH if
+ *     HIP reported an error while enqueueing.  dlayer_last_error() returns a thread-local,
+ *     statically stored message for the last failing call on the calling thread.
+ *   - Shape granularity: head_dim in {32, 64, 128}; n_q_heads % n_kv_heads == 0; seq a
+ *     multiple of 64; every contraction (inner) dimension a multiple of 64 and every output
+ *     feature dimension a multiple of 8; feature counts of the element-wise kernels a multiple
+ *     of 8.
+ */
+#ifndef DLAYER_H
+#define DLAYER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DLAYER_OK 0
+#define DLAYER_ERR_INVALID (-1)
+#define DLAYER_ERR_DEVICE (-2)
+#define DLAYER_ERR_LAUNCH (-3)
+
+/* Host-side description of one decoder layer call. */
+typedef struct dlayer_cfg {
+  int32_t batch, seq, d_model, n_q_heads, n_kv_heads, head_dim, d_ff;
+  float rms_eps;       /* added to the mean square inside the square root          */
+  float rope_base;     /* rotary base: angle(p, i) = p * rope_base^(-2 i / head_dim) */
+  int32_t rope_layout; /* 0: element i pairs with i + head_dim/2; 1: 2i pairs with 2i+1 */
+} dlayer_cfg;
+
+/* Device pointers to the nine parameter tensors of a layer (bf16):
+ * g_attn [D], wq [Hq*dh, D], wk [Hkv*dh, D], wv [Hkv*dh, D], wo [D, Hq*dh],
+ * g_mlp [D], w_gate [F, D], w_up [F, D], w_down [D, F].                                   */
+typedef struct dlayer_weights {
+  const void *g_attn, *wq, *wk, *wv, *wo, *g_mlp, *w_gate, *w_up, *w_down;
+} dlayer_weights;
+/* Same shapes, written by dlayer_backward (bf16). */
+typedef struct dlayer_wgrads {
+  void *g_attn, *wq, *wk, *wv, *wo, *g_mlp, *w_gate, *w_up, *w_down;
+} dlayer_wgrads;
+
+int dlayer_version(void);
+const char* dlayer_last_error(void);
+
+/* Bytes of the `saved` buffer that carries activations from dlayer_forward to
+ * dlayer_backward, and of the scratch `workspace` either call needs.  Return 0 for a
+ * configuration the library rejects (see shape granularity above).                          */
+size_t dlayer_saved_bytes(const dlayer_cfg* cfg);
+size_t dlayer_workspace_bytes(const dlayer_cfg* cfg);
+
+/*
+ * Forward of one decoder layer (the transformer block of the paper's benchmark model):
+ *   h1 = RMSNorm(x; g_attn);  q,k,v = h1 Wq^T, h1 Wk^T, h1 Wv^T;  q,k <- RoPE(q), RoPE(k)
+ *   o_h = softmax(q_h k_j^T / sqrt(head_dim) + causal mask) v_j,  j = h / (Hq/Hkv)
+ *   y1 = x + o Wo^T;  h2 = RMSNorm(y1; g_mlp);  y = y1 + (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T
+ * RMSNorm(t; g) = t * (mean_d t^2 + rms_eps)^(-1/2) * g.  Positions restart at 0 for every
+ * batch row.  x [T, D] bf16 (read only) -> y [T, D] bf16.  `saved` receives everything the
+ * backward needs.  x and y must not overlap.
+ */
+int dlayer_forward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w, void* y,
+                   void* saved, void* workspace, void* stream);
+
+/*
+ * Backward of dlayer_forward for upstream gradient dy [T, D] bf16: writes dx [T, D] bf16 and
+ * the nine parameter gradients (each summed over all T tokens; fp32 accumulation, bf16
+ * result).  accumulate_wgrads = 0 overwrites the gradient tensors; 1 adds to their current
+ * contents.  x, w and saved must be those of the matching forward call.
+ */
+int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w,
+                    const void* dy, const void* saved, void* dx, const dlayer_wgrads* dw,
+                    int accumulate_wgrads, void* workspace, void* stream);
+
+/*
+ * Mean softmax cross-entropy over T rows of V logits and its gradient (training loss of the
+ * paper's Fig. 2a, next-token objective):
+ *   loss = (1/T) sum_t ( logsumexp(logits[t, :]) - logits[t, targets[t]] )     -> *loss (device f32)
+ *   dlogits[t, v] = (softmax(logits[t, :])[v] - [v == targets[t]]) * grad_scale / T   (bf16)
+ * logits [T, V] bf16, targets [T] int64 with 0 <= target < V (out-of-range targets contribute
+ * only the logsumexp term and no -1).  dlogits may alias logits.  V % 8 == 0.
+ * workspace: ce_loss_workspace_bytes(T, V).
+ */
+size_t ce_loss_workspace_bytes(int64_t T, int64_t V);
+int ce_loss_fwd_bwd(const void* logits, const int64_t* targets, int64_t T, int64_t V,
+                    float grad_scale, float* loss, void* dlogits, void* workspace, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Building blocks (the steps of the layer, exposed for the model stack around it: embedding,
+ * final norm, LM head - and for step-by-step verification).
+ * ------------------------------------------------------------------------------------------ */
+
+/* h[t,:] = x[t,:] * rstd[t] * gamma,  rstd[t] = (mean_d x[t,d]^2 + eps)^(-1/2).
+ * x, h [T, D] bf16; gamma [D] bf16; rstd [T] f32 (written).  D % 8 == 0, D <= 16384.        */
+int rmsnorm_forward(const void* x, const void* gamma, int64_t T, int64_t D, float eps, void* h,
+                    float* rstd, void* stream);
+
+/* Gradient of rmsnorm_forward given dh [T, D] bf16 and the saved rstd:
+ *   xhat = x*rstd; dgamma = sum_t dh*xhat; dxhat = dh*gamma;
+ *   dx = rstd*(dxhat - xhat*mean_d(dxhat*xhat)) + (dres ? dres : 0)
+ * dres [T, D] bf16 is an optional gradient arriving through a residual connection (may be
+ * NULL; may alias dx).  dgamma [D] bf16; accumulate_dgamma as in dlayer_backward.
+ * workspace: rmsnorm_backward_workspace_bytes(T, D).                                        */
+size_t rmsnorm_backward_workspace_bytes(int64_t T, int64_t D);
+int rmsnorm_backward(const void* x, const void* gamma, const float* rstd, const void* dh,
+                     const void* dres, int64_t T, int64_t D, void* dx, void* dgamma,
+                     int accumulate_dgamma, void* workspace, void* stream);
+
+/* y = x W^T (+ residual).  x [T, K], w [N, K], residual [T, N] or NULL, y [T, N]; all bf16.
+ * K % 64 == 0, N % 8 == 0.  y may alias residual.                                           */
+int linear_forward(const void* x, const void* w, const void* residual, int64_t T, int64_t K,
+                   int64_t N, void* y, void* stream);
+
+/* Gradients of y = x W^T: dx = dy W ([T, K], skipped if dx == NULL) and dw = dy^T x ([N, K],
+ * skipped if dw == NULL).  T, K, N multiples of 64.  workspace:
+ * linear_backward_workspace_bytes(T, K, N).                                                 */
+size_t linear_backward_workspace_bytes(int64_t T, int64_t K, int64_t N);
+int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int64_t K,
+                    int64_t N, void* dx, void* dw, int accumulate_dw, void* workspace,
+                    void* stream);
+
+/* Rotary embedding applied in place to z [B*S, H, head_dim] bf16 (see dlayer_cfg for the angle
+ * and the two pairings); inverse != 0 rotates by the negative angle, which is the gradient
+ * map of the forward rotation.                                                              */
+int rope_apply(void* z, int64_t batch, int64_t seq, int64_t n_heads, int64_t head_dim,
+               float rope_base, int32_t rope_layout, int32_t inverse, void* stream);
+
+/* Causal softmax attention (definition at dlayer_forward).  q, o [B*S, Hq, dh]; k, v
+ * [B*S, Hkv, dh] bf16; lse [B, Hq, S] f32 = log-sum-exp of the scaled, masked score rows.   */
+int attention_forward(const void* q, const void* k, const void* v, int64_t batch, int64_t seq,
+                      int64_t n_q_heads, int64_t n_kv_heads, int64_t head_dim, void* o,
+                      float* lse, void* stream);
+
+/* Gradient of attention_forward: with P = exp(s - lse), dP = dO V^T, delta = rowsum(dO * O),
+ * dS = P * (dP - delta):  dV_j = sum_h P_h^T dO_h, dQ_h = dS_h K_j / sqrt(dh),
+ * dK_j = sum_h dS_h^T Q_h / sqrt(dh), sums over the query heads h of KV group j.
+ * workspace: attention_backward_workspace_bytes(...).                                       */
+size_t attention_backward_workspace_bytes(int64_t batch, int64_t seq, int64_t n_q_heads,
+                                          int64_t n_kv_heads, int64_t head_dim);
+int attention_backward(const void* q, const void* k, const void* v, const void* o,
+                       const void* d_o, const float* lse, int64_t batch, int64_t seq,
+                       int64_t n_q_heads, int64_t n_kv_heads, int64_t head_dim, void* dq,
+                       void* dk, void* dv, void* workspace, void* stream);
+
+/* a = silu(g) * u, silu(z) = z / (1 + exp(-z)); g, u, a [n] bf16, n % 8 == 0.                */
+int swiglu_forward(const void* g, const void* u, int64_t n, void* a, void* stream);
+/* dg = da * u * s * (1 + g * (1 - s)), du = da * g * s, s = 1/(1+exp(-g)).  dg may alias g,
+ * du may alias u.                                                                           */
+int swiglu_backward(const void* g, const void* u, const void* da, int64_t n, void* dg, void* du,
+                    void* stream);
+
+/* x0[t, :] = table[ids[t], :].  table [V, D] bf16, ids [T] int64 in [0, V), x0 [T, D] bf16.  */
+int embed_forward(const void* table, const int64_t* ids, int64_t T, int64_t V, int64_t D,
+                  void* x0, void* stream);
+/* dtable[v, :] = sum over t with ids[t] == v of dx0[t, :] (rows of absent ids are zero).
+ * Deterministic (no atomics): fp32 sum in token order, bf16 result.  dtable [V, D] bf16 is
+ * overwritten.                                                                              */
+int embed_backward(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D,
+                   void* dtable, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLAYER_H */

@@ -1,0 +1,208 @@
+"""ctypes binding for libdlayer.so.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(_PKG, "libdlayer.so")
+
+WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")
+
+EXPORTED_SYMBOLS = (
+    "dlayer_version", "dlayer_last_error", "dlayer_saved_bytes", "dlayer_workspace_bytes",
+    "dlayer_forward", "dlayer_backward", "ce_loss_workspace_bytes", "ce_loss_fwd_bwd",
+    "rmsnorm_forward", "rmsnorm_backward_workspace_bytes", "rmsnorm_backward",
+    "linear_forward", "linear_backward_workspace_bytes", "linear_backward", "rope_apply",
+    "attention_forward", "attention_backward_workspace_bytes", "attention_backward",
+    "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",
+)
+
+
+class DLayerError(RuntimeError):
+    pass
+
+
+class LayerCfg(C.Structure):
+    """Mirror of `dlayer_cfg`."""
+    _fields_ = [("batch", C.c_int32), ("seq", C.c_int32), ("d_model", C.c_int32),
+                ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("d_ff", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float),
+                ("rope_layout", C.c_int32)]
+
+    @classmethod
+    def of(cls, cfg) -> "LayerCfg":
+        """Accepts a LayerCfg or any object with the same attribute names."""
+        if isinstance(cfg, cls):
+            return cfg
+        return cls(*(getattr(cfg, n) for n, _ in cls._fields_))
+
+
+class _Ptrs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+def _load():
+    if not os.path.exists(lib_path):
+        raise DLayerError(
+            f"{lib_path} is missing: build it first (python -m paper_2602_08387_amd.build); "
+            "there is no fallback implementation")
+    l = C.CDLL(lib_path)
+    vp, i64, sz, i32, f32 = C.c_void_p, C.c_int64, C.c_size_t, C.c_int32, C.c_float
+    cfgp = C.POINTER(LayerCfg)
+    ptrs = C.POINTER(_Ptrs)
+    sig = {
+        "dlayer_version": (C.c_int, []),
+        "dlayer_last_error": (C.c_char_p, []),
+        "dlayer_saved_bytes": (sz, [cfgp]),
+        "dlayer_workspace_bytes": (sz, [cfgp]),
+        "dlayer_forward": (C.c_int, [cfgp, vp, ptrs, vp, vp, vp, vp]),
+        "dlayer_backward": (C.c_int, [cfgp, vp, ptrs, vp, vp, vp, ptrs, C.c_int, vp, vp]),
+        "ce_loss_workspace_bytes": (sz, [i64, i64]),
+        "ce_loss_fwd_bwd": (C.c_int, [vp, vp, i64, i64, f32, vp, vp, vp, vp]),
+        "rmsnorm_forward": (C.c_int, [vp, vp, i64, i64, f32, vp, vp, vp]),
+        "rmsnorm_backward_workspace_bytes": (sz, [i64, i64]),
+        "rmsnorm_backward": (C.c_int, [vp, vp, vp, vp, vp, i64, i64, vp, vp, C.c_int, vp, vp]),
+        "linear_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp]),
+        "linear_backward_workspace_bytes": (sz, [i64, i64, i64]),
+        "linear_backward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp, C.c_int, vp, vp]),
+        "rope_apply": (C.c_int, [vp, i64, i64, i64, i64, f32, i32, i32, vp]),
+        "attention_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp]),
+        "attention_backward_workspace_bytes": (sz, [i64, i64, i64, i64, i64]),
+        "attention_backward": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp]),
+        "swiglu_forward": (C.c_int, [vp, vp, i64, vp, vp]),
+        "swiglu_backward": (C.c_int, [vp, vp, vp, i64, vp, vp, vp]),
+        "embed_forward": (C.c_int, [vp, vp, i64, i64, i64, vp, vp]),
+        "embed_backward": (C.c_int, [vp, vp, i64, i64, i64, vp, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(l, name)
+        fn.restype = res
+        fn.argtypes = args
+    return l
+
+
+lib = _load()
+
+
+def _p(t):
+    """Device pointer of a torch tensor (or None -> NULL).  Tensors must be contiguous."""
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise DLayerError("tensor arguments must be contiguous")
+    if not t.is_cuda:
+        raise DLayerError("tensor arguments must live on the GPU")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc, name):
+    if rc != 0:
+        raise DLayerError(f"{name} failed with status {rc}: {lib.dlayer_last_error().decode()}")
+
+
+def _ptr_struct(d):
+    return _Ptrs(*(_p(d[n]) for n in WEIGHT_FIELDS))
+
+
+def dlayer_version() -> int:
+    return lib.dlayer_version()
+
+
+def dlayer_saved_bytes(cfg) -> int:
+    return lib.dlayer_saved_bytes(C.byref(LayerCfg.of(cfg)))
+
+
+def dlayer_workspace_bytes(cfg) -> int:
+    return lib.dlayer_workspace_bytes(C.byref(LayerCfg.of(cfg)))
+
+
+def dlayer_forward(cfg, x, weights, y, saved, workspace, stream=None):
+    _check(lib.dlayer_forward(C.byref(LayerCfg.of(cfg)), _p(x), C.byref(_ptr_struct(weights)), _p(y),
+                              _p(saved), _p(workspace), _stream(stream)), "dlayer_forward")
+
+
+def dlayer_backward(cfg, x, weights, dy, saved, dx, wgrads, accumulate_wgrads, workspace, stream=None):
+    _check(lib.dlayer_backward(C.byref(LayerCfg.of(cfg)), _p(x), C.byref(_ptr_struct(weights)), _p(dy),
+                               _p(saved), _p(dx), C.byref(_ptr_struct(wgrads)), int(accumulate_wgrads),
+                               _p(workspace), _stream(stream)), "dlayer_backward")
+
+
+def ce_loss_workspace_bytes(T, V) -> int:
+    return lib.ce_loss_workspace_bytes(T, V)
+
+
+def ce_loss_fwd_bwd(logits, targets, T, V, grad_scale, loss, dlogits, workspace, stream=None):
+    _check(lib.ce_loss_fwd_bwd(_p(logits), _p(targets), T, V, grad_scale, _p(loss), _p(dlogits),
+                               _p(workspace), _stream(stream)), "ce_loss_fwd_bwd")
+
+
+def rmsnorm_forward(x, gamma, T, D, eps, h, rstd, stream=None):
+    _check(lib.rmsnorm_forward(_p(x), _p(gamma), T, D, eps, _p(h), _p(rstd), _stream(stream)),
+           "rmsnorm_forward")
+
+
+def rmsnorm_backward_workspace_bytes(T, D) -> int:
+    return lib.rmsnorm_backward_workspace_bytes(T, D)
+
+
+def rmsnorm_backward(x, gamma, rstd, dh, dres, T, D, dx, dgamma, accumulate_dgamma, workspace, stream=None):
+    _check(lib.rmsnorm_backward(_p(x), _p(gamma), _p(rstd), _p(dh), _p(dres), T, D, _p(dx), _p(dgamma),
+                                int(accumulate_dgamma), _p(workspace), _stream(stream)), "rmsnorm_backward")
+
+
+def linear_forward(x, w, residual, T, K, N, y, stream=None):
+    _check(lib.linear_forward(_p(x), _p(w), _p(residual), T, K, N, _p(y), _stream(stream)), "linear_forward")
+
+
+def linear_backward_workspace_bytes(T, K, N) -> int:
+    return lib.linear_backward_workspace_bytes(T, K, N)
+
+
+def linear_backward(x, w, dy, T, K, N, dx, dw, accumulate_dw, workspace, stream=None):
+    _check(lib.linear_backward(_p(x), _p(w), _p(dy), T, K, N, _p(dx), _p(dw), int(accumulate_dw),
+                               _p(workspace), _stream(stream)), "linear_backward")
+
+
+def rope_apply(z, batch, seq, n_heads, head_dim, rope_base, rope_layout, inverse, stream=None):
+    _check(lib.rope_apply(_p(z), batch, seq, n_heads, head_dim, rope_base, rope_layout, int(inverse),
+                          _stream(stream)), "rope_apply")
+
+
+def attention_forward(q, k, v, batch, seq, n_q_heads, n_kv_heads, head_dim, o, lse, stream=None):
+    _check(lib.attention_forward(_p(q), _p(k), _p(v), batch, seq, n_q_heads, n_kv_heads, head_dim, _p(o),
+                                 _p(lse), _stream(stream)), "attention_forward")
+
+
+def attention_backward_workspace_bytes(batch, seq, n_q_heads, n_kv_heads, head_dim) -> int:
+    return lib.attention_backward_workspace_bytes(batch, seq, n_q_heads, n_kv_heads, head_dim)
+
+
+def attention_backward(q, k, v, o, d_o, lse, batch, seq, n_q_heads, n_kv_heads, head_dim, dq, dk, dv,
+                       workspace, stream=None):
+    _check(lib.attention_backward(_p(q), _p(k), _p(v), _p(o), _p(d_o), _p(lse), batch, seq, n_q_heads,
+                                  n_kv_heads, head_dim, _p(dq), _p(dk), _p(dv), _p(workspace),
+                                  _stream(stream)), "attention_backward")
+
+
+def swiglu_forward(g, u, n, a, stream=None):
+    _check(lib.swiglu_forward(_p(g), _p(u), n, _p(a), _stream(stream)), "swiglu_forward")
+
+
+def swiglu_backward(g, u, da, n, dg, du, stream=None):
+    _check(lib.swiglu_backward(_p(g), _p(u), _p(da), n, _p(dg), _p(du), _stream(stream)), "swiglu_backward")
+
+
+def embed_forward(table, ids, T, V, D, x0, stream=None):
+    _check(lib.embed_forward(_p(table), _p(ids), T, V, D, _p(x0), _stream(stream)), "embed_forward")
+
+
+def embed_backward(dx0, ids, T, V, D, dtable, stream=None):
+    _check(lib.embed_backward(_p(dx0), _p(ids), T, V, D, _p(dtable), _stream(stream)), "embed_backward")

@@ -1,0 +1,406 @@
+// C-ABI entry points declared in include/dlayer.h: argument validation, buffer carving and the
+// order of kernel launches.  No arithmetic of the layer lives here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/dlayer.h"
+#include "common.h"
+#include "kernels.h"
+
+namespace dl {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(DLAYER_ERR_LAUNCH, "%s: %s", what, hipGetErrorString(e));
+  return 0;
+}
+
+static int check_device() {
+  static thread_local int cached_dev = -1;
+  static thread_local int cached_ok = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return fail(DLAYER_ERR_DEVICE, "no HIP device is current");
+  if (dev != cached_dev) {
+    hipDeviceProp_t p;
+    if (hipGetDeviceProperties(&p, dev) != hipSuccess) return fail(DLAYER_ERR_DEVICE, "cannot query device %d", dev);
+    cached_dev = dev;
+    cached_ok = strncmp(p.gcnArchName, "gfx950", 6) == 0;
+    if (!cached_ok) return fail(DLAYER_ERR_DEVICE, "device %d is %s; this library is built for gfx950 only", dev, p.gcnArchName);
+  }
+  if (!cached_ok) return fail(DLAYER_ERR_DEVICE, "device %d is not gfx950", dev);
+  return 0;
+}
+
+#define REQUIRE(cond, ...) \
+  do { if (!(cond)) return dl::fail(DLAYER_ERR_INVALID, __VA_ARGS__); } while (0)
+#define REQUIRE_PTR(p) REQUIRE((p) != nullptr && dl::aligned16(p), "%s: pointer %s is null or not 16-byte aligned", __func__, #p)
+#define TRY(x) do { int rc_ = (x); if (rc_) return rc_; } while (0)
+
+static inline size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* p) : base((char*)p) {}
+  void* take(size_t bytes) { void* r = base ? base + off : nullptr; off += up256(bytes); return r; }
+};
+
+static const char* cfg_problem(const dlayer_cfg* c) {
+  if (!c) return "cfg is null";
+  if (c->batch <= 0 || c->seq <= 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->d_ff <= 0)
+    return "non-positive dimension";
+  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return "head_dim must be 32, 64 or 128";
+  if (c->n_q_heads % c->n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
+  if (c->seq % 128) return "seq must be a multiple of 128";
+  if (c->d_model % 64 || c->d_ff % 64) return "d_model and d_ff must be multiples of 64";
+  if (c->d_model > 4096 * 4) return "d_model above 16384 is not supported";
+  if (c->rope_layout != 0 && c->rope_layout != 1) return "rope_layout must be 0 or 1";
+  if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return "rms_eps must be >= 0 and rope_base > 0";
+  const int64_t T = (int64_t)c->batch * c->seq;
+  const int64_t widest = c->d_ff > c->n_q_heads * c->head_dim ? c->d_ff : (int64_t)c->n_q_heads * c->head_dim;
+  if (T * widest * 2 >= ((int64_t)1 << 32) || T * c->d_model * 2 >= ((int64_t)1 << 32))
+    return "an activation tensor reaches 4 GiB";
+  return nullptr;
+}
+
+struct Saved {
+  float *rstd1, *rstd2, *lse;
+  void *h1, *q, *k, *v, *o, *y1, *h2, *g, *u, *a;
+  size_t bytes;
+};
+static Saved carve_saved(const dlayer_cfg* c, void* p) {
+  const size_t T = (size_t)c->batch * c->seq, D = c->d_model, F = c->d_ff;
+  const size_t QD = (size_t)c->n_q_heads * c->head_dim, KD = (size_t)c->n_kv_heads * c->head_dim;
+  Carver cv(p);
+  Saved s;
+  s.rstd1 = (float*)cv.take(T * 4);
+  s.rstd2 = (float*)cv.take(T * 4);
+  s.lse = (float*)cv.take(T * c->n_q_heads * 4);
+  s.h1 = cv.take(T * D * 2);
+  s.q = cv.take(T * QD * 2);
+  s.k = cv.take(T * KD * 2);
+  s.v = cv.take(T * KD * 2);
+  s.o = cv.take(T * QD * 2);
+  s.y1 = cv.take(T * D * 2);
+  s.h2 = cv.take(T * D * 2);
+  s.g = cv.take(T * F * 2);
+  s.u = cv.take(T * F * 2);
+  s.a = cv.take(T * F * 2);
+  s.bytes = cv.off;
+  return s;
+}
+
+struct Work {
+  void *da_dg, *du, *dh2, *dy1, *d_o, *dq, *dk, *dv, *dh1, *attn_ws, *rms_ws;
+  size_t bytes;
+};
+static Work carve_work(const dlayer_cfg* c, void* p) {
+  const size_t T = (size_t)c->batch * c->seq, D = c->d_model, F = c->d_ff;
+  const size_t QD = (size_t)c->n_q_heads * c->head_dim, KD = (size_t)c->n_kv_heads * c->head_dim;
+  Carver cv(p);
+  Work w;
+  w.da_dg = cv.take(T * F * 2);
+  w.du = cv.take(T * F * 2);
+  w.dh2 = cv.take(T * D * 2);
+  w.dy1 = cv.take(T * D * 2);
+  w.d_o = cv.take(T * QD * 2);
+  w.dq = cv.take(T * QD * 2);
+  w.dk = cv.take(T * KD * 2);
+  w.dv = cv.take(T * KD * 2);
+  w.dh1 = cv.take(T * D * 2);
+  w.attn_ws = cv.take(attention_bwd_workspace(c->batch, c->seq, c->n_q_heads, c->n_kv_heads, c->head_dim));
+  w.rms_ws = cv.take(rmsnorm_bwd_workspace(T, D));
+  w.bytes = cv.off;
+  return w;
+}
+
+// y[T,N] = x[T,K] W[N,K]^T (+ residual)
+static int gemm_nt(const void* x, const void* w, const void* res, int64_t T, int64_t K, int64_t N, void* y,
+                   hipStream_t st) {
+  GemmArgs g{};
+  g.nseg = 1;
+  g.seg[0] = {x, w, K, K, (int)K};
+  g.M = (int)T; g.N = (int)N; g.c = y; g.ldc = N; g.r = res; g.accumulate = 0;
+  g.a_kmajor = true; g.b_kmajor = true;
+  return launch_gemm(g, st);
+}
+// dx[T,K] = sum_s dy_s[T,N_s] W_s[N_s,K]
+static int gemm_dgrad(int nseg, const void* const* dy, const void* const* w, const int64_t* Ns, int64_t T,
+                      int64_t K, void* dx, hipStream_t st) {
+  GemmArgs g{};
+  g.nseg = nseg;
+  for (int s = 0; s < nseg; ++s) g.seg[s] = {dy[s], w[s], Ns[s], K, (int)Ns[s]};
+  g.M = (int)T; g.N = (int)K; g.c = dx; g.ldc = K; g.r = nullptr; g.accumulate = 0;
+  g.a_kmajor = true; g.b_kmajor = false;
+  return launch_gemm(g, st);
+}
+// dw[N,K] (+)= dy[T,N]^T x[T,K]
+static int gemm_wgrad(const void* dy, const void* x, int64_t T, int64_t N, int64_t K, void* dw, int accumulate,
+                      hipStream_t st) {
+  GemmArgs g{};
+  g.nseg = 1;
+  g.seg[0] = {dy, x, N, K, (int)T};
+  g.M = (int)N; g.N = (int)K; g.c = dw; g.ldc = K; g.r = nullptr; g.accumulate = accumulate;
+  g.a_kmajor = false; g.b_kmajor = false;
+  return launch_gemm(g, st);
+}
+
+}  // namespace dl
+
+using namespace dl;
+
+extern "C" {
+
+int dlayer_version(void) { return 1; }
+const char* dlayer_last_error(void) { return g_err; }
+
+size_t dlayer_saved_bytes(const dlayer_cfg* cfg) {
+  if (cfg_problem(cfg)) return 0;
+  return carve_saved(cfg, nullptr).bytes;
+}
+size_t dlayer_workspace_bytes(const dlayer_cfg* cfg) {
+  if (cfg_problem(cfg)) return 0;
+  return carve_work(cfg, nullptr).bytes;
+}
+
+int dlayer_forward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w, void* y, void* saved,
+                   void* workspace, void* stream) {
+  const char* prob = cfg_problem(cfg);
+  REQUIRE(!prob, "dlayer_forward: %s", prob);
+  REQUIRE(w != nullptr, "dlayer_forward: weights struct is null");
+  REQUIRE_PTR(x); REQUIRE_PTR(y); REQUIRE_PTR(saved); REQUIRE_PTR(workspace);
+  REQUIRE_PTR(w->g_attn); REQUIRE_PTR(w->wq); REQUIRE_PTR(w->wk); REQUIRE_PTR(w->wv); REQUIRE_PTR(w->wo);
+  REQUIRE_PTR(w->g_mlp); REQUIRE_PTR(w->w_gate); REQUIRE_PTR(w->w_up); REQUIRE_PTR(w->w_down);
+  REQUIRE(x != y, "dlayer_forward: x and y must not overlap");
+  TRY(check_device());
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t B = cfg->batch, S = cfg->seq, T = B * S, D = cfg->d_model, F = cfg->d_ff;
+  const int64_t Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, dh = cfg->head_dim, QD = Hq * dh, KD = Hkv * dh;
+  Saved s = carve_saved(cfg, saved);
+  TRY(launch_rmsnorm_fwd(x, w->g_attn, T, D, cfg->rms_eps, s.h1, s.rstd1, st));
+  TRY(gemm_nt(s.h1, w->wq, nullptr, T, D, QD, s.q, st));
+  TRY(gemm_nt(s.h1, w->wk, nullptr, T, D, KD, s.k, st));
+  TRY(gemm_nt(s.h1, w->wv, nullptr, T, D, KD, s.v, st));
+  TRY(launch_rope(s.q, B, S, Hq, dh, cfg->rope_base, cfg->rope_layout, 0, st));
+  TRY(launch_rope(s.k, B, S, Hkv, dh, cfg->rope_base, cfg->rope_layout, 0, st));
+  TRY(launch_attention_fwd(s.q, s.k, s.v, B, S, Hq, Hkv, dh, s.o, s.lse, st));
+  TRY(gemm_nt(s.o, w->wo, x, T, QD, D, s.y1, st));
+  TRY(launch_rmsnorm_fwd(s.y1, w->g_mlp, T, D, cfg->rms_eps, s.h2, s.rstd2, st));
+  TRY(gemm_nt(s.h2, w->w_gate, nullptr, T, D, F, s.g, st));
+  TRY(gemm_nt(s.h2, w->w_up, nullptr, T, D, F, s.u, st));
+  TRY(launch_swiglu_fwd(s.g, s.u, T * F, s.a, st));
+  TRY(gemm_nt(s.a, w->w_down, s.y1, T, F, D, y, st));
+  return DLAYER_OK;
+}
+
+int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w, const void* dy,
+                    const void* saved, void* dx, const dlayer_wgrads* dw, int accumulate_wgrads,
+                    void* workspace, void* stream) {
+  const char* prob = cfg_problem(cfg);
+  REQUIRE(!prob, "dlayer_backward: %s", prob);
+  REQUIRE(w != nullptr && dw != nullptr, "dlayer_backward: weights or gradient struct is null");
+  REQUIRE_PTR(x); REQUIRE_PTR(dy); REQUIRE_PTR(saved); REQUIRE_PTR(dx); REQUIRE_PTR(workspace);
+  REQUIRE_PTR(w->g_attn); REQUIRE_PTR(w->wq); REQUIRE_PTR(w->wk); REQUIRE_PTR(w->wv); REQUIRE_PTR(w->wo);
+  REQUIRE_PTR(w->g_mlp); REQUIRE_PTR(w->w_gate); REQUIRE_PTR(w->w_up); REQUIRE_PTR(w->w_down);
+  REQUIRE_PTR(dw->g_attn); REQUIRE_PTR(dw->wq); REQUIRE_PTR(dw->wk); REQUIRE_PTR(dw->wv); REQUIRE_PTR(dw->wo);
+  REQUIRE_PTR(dw->g_mlp); REQUIRE_PTR(dw->w_gate); REQUIRE_PTR(dw->w_up); REQUIRE_PTR(dw->w_down);
+  TRY(check_device());
+  hipStream_t st = (hipStream_t)stream;
+  const int acc = accumulate_wgrads ? 1 : 0;
+  const int64_t B = cfg->batch, S = cfg->seq, T = B * S, D = cfg->d_model, F = cfg->d_ff;
+  const int64_t Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, dh = cfg->head_dim, QD = Hq * dh, KD = Hkv * dh;
+  Saved s = carve_saved(cfg, const_cast<void*>(saved));
+  Work k = carve_work(cfg, workspace);
+  // y = y1 + a Wd^T
+  {
+    const void* dys[1] = {dy}; const void* ws[1] = {w->w_down}; const int64_t ns[1] = {D};
+    TRY(gemm_dgrad(1, dys, ws, ns, T, F, k.da_dg, st));
+  }
+  TRY(gemm_wgrad(dy, s.a, T, D, F, dw->w_down, acc, st));
+  TRY(launch_swiglu_bwd(s.g, s.u, k.da_dg, T * F, k.da_dg, k.du, st));
+  {
+    const void* dys[2] = {k.da_dg, k.du}; const void* ws[2] = {w->w_gate, w->w_up}; const int64_t ns[2] = {F, F};
+    TRY(gemm_dgrad(2, dys, ws, ns, T, D, k.dh2, st));
+  }
+  TRY(gemm_wgrad(k.da_dg, s.h2, T, F, D, dw->w_gate, acc, st));
+  TRY(gemm_wgrad(k.du, s.h2, T, F, D, dw->w_up, acc, st));
+  TRY(launch_rmsnorm_bwd(s.y1, w->g_mlp, s.rstd2, k.dh2, dy, T, D, k.dy1, dw->g_mlp, acc, k.rms_ws, st));
+  // y1 = x + o Wo^T
+  {
+    const void* dys[1] = {k.dy1}; const void* ws[1] = {w->wo}; const int64_t ns[1] = {D};
+    TRY(gemm_dgrad(1, dys, ws, ns, T, QD, k.d_o, st));
+  }
+  TRY(gemm_wgrad(k.dy1, s.o, T, D, QD, dw->wo, acc, st));
+  TRY(launch_attention_bwd(s.q, s.k, s.v, s.o, k.d_o, s.lse, B, S, Hq, Hkv, dh, k.dq, k.dk, k.dv, k.attn_ws, st));
+  TRY(launch_rope(k.dq, B, S, Hq, dh, cfg->rope_base, cfg->rope_layout, 1, st));
+  TRY(launch_rope(k.dk, B, S, Hkv, dh, cfg->rope_base, cfg->rope_layout, 1, st));
+  {
+    const void* dys[3] = {k.dq, k.dk, k.dv}; const void* ws[3] = {w->wq, w->wk, w->wv};
+    const int64_t ns[3] = {QD, KD, KD};
+    TRY(gemm_dgrad(3, dys, ws, ns, T, D, k.dh1, st));
+  }
+  TRY(gemm_wgrad(k.dq, s.h1, T, QD, D, dw->wq, acc, st));
+  TRY(gemm_wgrad(k.dk, s.h1, T, KD, D, dw->wk, acc, st));
+  TRY(gemm_wgrad(k.dv, s.h1, T, KD, D, dw->wv, acc, st));
+  TRY(launch_rmsnorm_bwd(x, w->g_attn, s.rstd1, k.dh1, k.dy1, T, D, dx, dw->g_attn, acc, k.rms_ws, st));
+  return DLAYER_OK;
+}
+
+size_t ce_loss_workspace_bytes(int64_t T, int64_t V) { return T > 0 && V > 0 ? ce_workspace(T, V) : 0; }
+
+int ce_loss_fwd_bwd(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
+                    float* loss, void* dlogits, void* workspace, void* stream) {
+  REQUIRE(T > 0 && V > 0 && V % 8 == 0, "ce_loss_fwd_bwd: need T > 0, V > 0, V %% 8 == 0 (T=%lld V=%lld)", (long long)T, (long long)V);
+  REQUIRE(T < ((int64_t)1 << 31), "ce_loss_fwd_bwd: T too large");
+  REQUIRE_PTR(logits); REQUIRE_PTR(dlogits); REQUIRE_PTR(workspace);
+  REQUIRE(targets != nullptr && loss != nullptr, "ce_loss_fwd_bwd: targets or loss is null");
+  TRY(check_device());
+  return launch_ce(logits, targets, T, V, grad_scale, loss, dlogits, workspace, (hipStream_t)stream);
+}
+
+int rmsnorm_forward(const void* x, const void* gamma, int64_t T, int64_t D, float eps, void* h, float* rstd,
+                    void* stream) {
+  REQUIRE(T > 0 && D > 0 && D % 8 == 0 && D <= 16384, "rmsnorm_forward: need T > 0, D %% 8 == 0, D <= 16384");
+  REQUIRE_PTR(x); REQUIRE_PTR(gamma); REQUIRE_PTR(h);
+  REQUIRE(rstd != nullptr, "rmsnorm_forward: rstd is null");
+  TRY(check_device());
+  return launch_rmsnorm_fwd(x, gamma, T, D, eps, h, rstd, (hipStream_t)stream);
+}
+
+size_t rmsnorm_backward_workspace_bytes(int64_t T, int64_t D) { return T > 0 && D > 0 ? rmsnorm_bwd_workspace(T, D) : 0; }
+
+int rmsnorm_backward(const void* x, const void* gamma, const float* rstd, const void* dh, const void* dres,
+                     int64_t T, int64_t D, void* dx, void* dgamma, int accumulate_dgamma, void* workspace,
+                     void* stream) {
+  REQUIRE(T > 0 && D > 0 && D % 8 == 0 && D <= 4096, "rmsnorm_backward: need T > 0, D %% 8 == 0, D <= 4096");
+  REQUIRE_PTR(x); REQUIRE_PTR(gamma); REQUIRE_PTR(dh); REQUIRE_PTR(dx); REQUIRE_PTR(workspace);
+  REQUIRE(dgamma != nullptr && rstd != nullptr, "rmsnorm_backward: dgamma or rstd is null");
+  REQUIRE(dres == nullptr || aligned16(dres), "rmsnorm_backward: dres is misaligned");
+  TRY(check_device());
+  return launch_rmsnorm_bwd(x, gamma, rstd, dh, dres, T, D, dx, dgamma, accumulate_dgamma ? 1 : 0, workspace,
+                            (hipStream_t)stream);
+}
+
+int linear_forward(const void* x, const void* w, const void* residual, int64_t T, int64_t K, int64_t N, void* y,
+                   void* stream) {
+  REQUIRE(T > 0 && K > 0 && N > 0 && K % 64 == 0 && N % 8 == 0, "linear_forward: need K %% 64 == 0 and N %% 8 == 0");
+  REQUIRE(T * K * 2 < ((int64_t)1 << 32) && N * K * 2 < ((int64_t)1 << 32) && T < (1 << 30) && N < (1 << 30),
+          "linear_forward: an operand reaches 4 GiB");
+  REQUIRE_PTR(x); REQUIRE_PTR(w); REQUIRE_PTR(y);
+  REQUIRE(residual == nullptr || aligned16(residual), "linear_forward: residual is misaligned");
+  TRY(check_device());
+  return gemm_nt(x, w, residual, T, K, N, y, (hipStream_t)stream);
+}
+
+size_t linear_backward_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
+
+int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int64_t K, int64_t N, void* dx,
+                    void* dw, int accumulate_dw, void* workspace, void* stream) {
+  (void)workspace;
+  REQUIRE(T > 0 && K > 0 && N > 0 && T % 64 == 0 && K % 64 == 0 && N % 64 == 0,
+          "linear_backward: T, K and N must be multiples of 64");
+  REQUIRE(T * K * 2 < ((int64_t)1 << 32) && N * K * 2 < ((int64_t)1 << 32) && T * N * 2 < ((int64_t)1 << 32),
+          "linear_backward: an operand reaches 4 GiB");
+  REQUIRE_PTR(x); REQUIRE_PTR(w); REQUIRE_PTR(dy);
+  REQUIRE((dx == nullptr || aligned16(dx)) && (dw == nullptr || aligned16(dw)), "linear_backward: misaligned output");
+  TRY(check_device());
+  hipStream_t st = (hipStream_t)stream;
+  if (dx) {
+    const void* dys[1] = {dy}; const void* ws[1] = {w}; const int64_t ns[1] = {N};
+    TRY(gemm_dgrad(1, dys, ws, ns, T, K, dx, st));
+  }
+  if (dw) TRY(gemm_wgrad(dy, x, T, N, K, dw, accumulate_dw ? 1 : 0, st));
+  return DLAYER_OK;
+}
+
+int rope_apply(void* z, int64_t batch, int64_t seq, int64_t n_heads, int64_t head_dim, float rope_base,
+               int32_t rope_layout, int32_t inverse, void* stream) {
+  REQUIRE(batch > 0 && seq > 0 && n_heads > 0, "rope_apply: non-positive dimension");
+  REQUIRE(head_dim == 32 || head_dim == 64 || head_dim == 128, "rope_apply: head_dim must be 32, 64 or 128");
+  REQUIRE(rope_layout == 0 || rope_layout == 1, "rope_apply: rope_layout must be 0 or 1");
+  REQUIRE(rope_base > 0.f, "rope_apply: rope_base must be positive");
+  REQUIRE_PTR(z);
+  TRY(check_device());
+  return launch_rope(z, batch, seq, n_heads, head_dim, rope_base, rope_layout, inverse ? 1 : 0, (hipStream_t)stream);
+}
+
+static int attn_shape_ok(int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t dh, const char* who) {
+  REQUIRE(B > 0 && S > 0 && Hq > 0 && Hkv > 0, "%s: non-positive dimension", who);
+  REQUIRE(dh == 32 || dh == 64 || dh == 128, "%s: head_dim must be 32, 64 or 128", who);
+  REQUIRE(Hq % Hkv == 0, "%s: n_q_heads must be a multiple of n_kv_heads", who);
+  REQUIRE(S % 128 == 0, "%s: seq must be a multiple of 128", who);
+  REQUIRE(B * S * Hq * dh * 2 < ((int64_t)1 << 32), "%s: q reaches 4 GiB", who);
+  REQUIRE(B < 65536 && Hq < 65536, "%s: batch or head count too large", who);
+  return 0;
+}
+
+int attention_forward(const void* q, const void* k, const void* v, int64_t batch, int64_t seq, int64_t n_q_heads,
+                      int64_t n_kv_heads, int64_t head_dim, void* o, float* lse, void* stream) {
+  TRY(attn_shape_ok(batch, seq, n_q_heads, n_kv_heads, head_dim, "attention_forward"));
+  REQUIRE_PTR(q); REQUIRE_PTR(k); REQUIRE_PTR(v); REQUIRE_PTR(o);
+  REQUIRE(lse != nullptr, "attention_forward: lse is null");
+  TRY(check_device());
+  return launch_attention_fwd(q, k, v, batch, seq, n_q_heads, n_kv_heads, head_dim, o, lse, (hipStream_t)stream);
+}
+
+size_t attention_backward_workspace_bytes(int64_t batch, int64_t seq, int64_t n_q_heads, int64_t n_kv_heads,
+                                          int64_t head_dim) {
+  if (batch <= 0 || seq <= 0 || n_q_heads <= 0) return 0;
+  return attention_bwd_workspace(batch, seq, n_q_heads, n_kv_heads, head_dim);
+}
+
+int attention_backward(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                       const float* lse, int64_t batch, int64_t seq, int64_t n_q_heads, int64_t n_kv_heads,
+                       int64_t head_dim, void* dq, void* dk, void* dv, void* workspace, void* stream) {
+  TRY(attn_shape_ok(batch, seq, n_q_heads, n_kv_heads, head_dim, "attention_backward"));
+  REQUIRE_PTR(q); REQUIRE_PTR(k); REQUIRE_PTR(v); REQUIRE_PTR(o); REQUIRE_PTR(d_o);
+  REQUIRE_PTR(dq); REQUIRE_PTR(dk); REQUIRE_PTR(dv); REQUIRE_PTR(workspace);
+  REQUIRE(lse != nullptr, "attention_backward: lse is null");
+  TRY(check_device());
+  return launch_attention_bwd(q, k, v, o, d_o, lse, batch, seq, n_q_heads, n_kv_heads, head_dim, dq, dk, dv,
+                              workspace, (hipStream_t)stream);
+}
+
+int swiglu_forward(const void* g, const void* u, int64_t n, void* a, void* stream) {
+  REQUIRE(n > 0 && n % 8 == 0, "swiglu_forward: n must be a positive multiple of 8");
+  REQUIRE_PTR(g); REQUIRE_PTR(u); REQUIRE_PTR(a);
+  TRY(check_device());
+  return launch_swiglu_fwd(g, u, n, a, (hipStream_t)stream);
+}
+
+int swiglu_backward(const void* g, const void* u, const void* da, int64_t n, void* dg, void* du, void* stream) {
+  REQUIRE(n > 0 && n % 8 == 0, "swiglu_backward: n must be a positive multiple of 8");
+  REQUIRE_PTR(g); REQUIRE_PTR(u); REQUIRE_PTR(da); REQUIRE_PTR(dg); REQUIRE_PTR(du);
+  TRY(check_device());
+  return launch_swiglu_bwd(g, u, da, n, dg, du, (hipStream_t)stream);
+}
+
+int embed_forward(const void* table, const int64_t* ids, int64_t T, int64_t V, int64_t D, void* x0, void* stream) {
+  REQUIRE(T > 0 && V > 0 && D > 0 && D % 8 == 0 && T < ((int64_t)1 << 31), "embed_forward: need T, V > 0 and D %% 8 == 0");
+  REQUIRE_PTR(table); REQUIRE_PTR(x0);
+  REQUIRE(ids != nullptr, "embed_forward: ids is null");
+  TRY(check_device());
+  return launch_embed_fwd(table, ids, T, V, D, x0, (hipStream_t)stream);
+}
+
+int embed_backward(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D, void* dtable,
+                   void* stream) {
+  REQUIRE(T > 0 && V > 0 && D > 0 && D % 8 == 0 && T < ((int64_t)1 << 31), "embed_backward: need T, V > 0 and D %% 8 == 0");
+  REQUIRE_PTR(dx0); REQUIRE_PTR(dtable);
+  REQUIRE(ids != nullptr, "embed_backward: ids is null");
+  TRY(check_device());
+  return launch_embed_bwd(dx0, ids, T, V, D, dtable, (hipStream_t)stream);
+}
+
+}  // extern "C"

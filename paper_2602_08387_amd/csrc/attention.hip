@@ -1,0 +1,536 @@
+// Causal softmax attention with grouped KV heads for gfx950: forward and backward, blockwise
+// ("flash") so that no S x S matrix is ever stored.  q, o [B*S, Hq, DH]; k, v [B*S, Hkv, DH].
+//
+// All products run on v_mfma_f32_32x32x16_bf16 and are arranged so that the score tile comes out
+// of the MFMA already in the register layout the next product consumes (no LDS round trip for
+// P or dS):
+//   forward / dQ kernel : S^T[kv][q] = K Q^T   -> lane owns one query column, keys along registers
+//                         O^T[d][q] += V^T P^T,  dQ^T[d][q] += K^T dS^T
+//   dK/dV kernel        : S[q][kv]  = Q K^T    -> lane owns one key column, queries along registers
+//                         dV^T[d][kv] += dO^T P,  dK^T[d][kv] += Q^T dS
+// Row statistics (max, sum, LSE, delta) then live one per lane in the first pair of kernels, and
+// the row reductions are an in-lane loop plus one exchange between lane l and lane l^32.
+// The "transposed" operands (V^T, K^T, dO^T, Q^T) are read from row-major LDS tiles with
+// ds_read_b64_tr_b16.  K/V (or Q/dO) tiles stream global -> LDS with buffer_load ... lds,
+// double buffered.
+//
+// An MFMA sums over its 16 k-slots in any order, so the slot -> key assignment is chosen to match
+// the accumulator layout of the score tile: for a 16-key step, slot (half = lane / 32, e = 0..7)
+// holds key 8*(e/4) + 4*half + e%4.  The transposed loads of the other operand use the same map.
+#include "common.h"
+#include "kernels.h"
+
+namespace dl {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// v_exp_f32: 2^x without the denormal-range fix-up (results below 2^-126 flush to zero, which is
+// what a softmax weight that small should be anyway).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t attn_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// [ROWS][DH] bf16 tile in LDS, DH*2 bytes per row, 16-byte chunk c of row r stored at chunk
+// c ^ (r & SWZ_MASK).  Loaded by NW waves with 1 KiB wave-wide async loads.
+template <int ROWS, int DH, int NW>
+struct RowTile {
+  static constexpr int ROW_B = DH * 2;
+  static constexpr int LPR = DH / 8;          // lanes (16 B chunks) per row
+  static constexpr int RPI = 1024 / ROW_B;    // rows per wave-wide load
+  static constexpr int NINSTR = ROWS / RPI;
+  static constexpr int PER_WAVE = NINSTR / NW;
+  static constexpr int SWZ_MASK = (LPR - 1) < 7 ? (LPR - 1) : 7;
+  static_assert(NINSTR % NW == 0 && ((ROWS / NW) % 8) == 0, "tile split");
+  static constexpr int BYTES = ROWS * ROW_B;
+
+  // rs describes memory starting at the tile's first row; ld = row stride in elements.
+  static __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, char* lds_tile, int wave,
+                                               int lane, int64_t ld) {
+    const int r = lane / LPR, pc = lane % LPR;
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+      const int j = wave * PER_WAVE + i;
+      const int c = pc ^ ((i * RPI + r) & SWZ_MASK);
+      const uint32_t vo = (uint32_t)(r * ld * 2 + (c << 4));
+      const uint32_t so = (uint32_t)((int64_t)j * RPI * ld * 2);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, vo, so, 0, 0);
+    }
+  }
+  // MFMA operand for rows row0 + lane%32, contraction over the DH index, step kk (16 of DH).
+  static __device__ __forceinline__ bf16x8 frag_rows(const char* t, int row0, int kk, int lane) {
+    const int row = row0 + (lane & 31);
+    const int c = (kk * 2 + (lane >> 5)) ^ (row & SWZ_MASK);
+    return *reinterpret_cast<const bf16x8*>(t + row * ROW_B + (c << 4));
+  }
+  // MFMA operand for "rows" = 32 columns of the tile starting at col0 (the DH index), contraction
+  // over 16 tile rows starting at krow0, with the slot -> row map described at the top of the file.
+  static __device__ __forceinline__ bf16x8 frag_cols(const char* t, int col0, int krow0, int lane) {
+    const int grp = lane >> 4, s = lane & 15, e = s >> 2, g = s & 3;
+    const int col = col0 + ((grp & 1) << 4) + (g << 2);
+    const int row = krow0 + ((grp >> 1) << 2) + e;
+    const char* p0 = t + row * ROW_B + ((((col >> 3) ^ (row & SWZ_MASK)) << 4) | ((col & 7) << 1));
+    const int row2 = row + 8;
+    const char* p1 = t + row2 * ROW_B + ((((col >> 3) ^ (row2 & SWZ_MASK)) << 4) | ((col & 7) << 1));
+    bf16x8 v;
+    v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p0));
+    v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p1));
+    return v;
+  }
+};
+
+__device__ __forceinline__ bf16x8 pack_slots(const f32x16& a, int first) {
+  bf16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (bf16_t)a[first + e];
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward.  Workgroup = 4 waves = 128 query rows of one (batch, query head); wave = 32 rows.
+// ------------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict__ q,
+                                                       const bf16_t* __restrict__ k,
+                                                       const bf16_t* __restrict__ v,
+                                                       bf16_t* __restrict__ o, float* __restrict__ lse,
+                                                       int S, int Hq, int Hkv, float scale_log2) {
+  using Tile = RowTile<64, DH, 4>;
+  constexpr int STAGE = 2 * Tile::BYTES;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int hk = h / (Hq / Hkv);
+  const int q0 = qt * 128, qw = q0 + wave * 32;
+  const int lq = lane & 31, half = lane >> 5;
+  const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
+
+  bf16x8 qf[DH / 16];
+  {
+    const bf16_t* qp = q + ((int64_t)b * S + qw + lq) * ldq + (int64_t)h * DH + half * 8;
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+  }
+  f32x16 oacc[DH / 32];
+#pragma unroll
+  for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+
+  const bf16_t* kb = k + (int64_t)b * S * ldk + (int64_t)hk * DH;
+  const bf16_t* vb = v + (int64_t)b * S * ldk + (int64_t)hk * DH;
+  const uint32_t kv_bytes = (uint32_t)((((int64_t)S - 1) * ldk + DH) * 2);
+  const int nkv = (q0 + 128) / 64;
+  // One buffer descriptor per tile: base at the tile's first key row, range to the end of this
+  // batch row's keys (rows past it would read as zero).
+  auto issue_tile = [&](int t, int stage) {
+    const uint32_t skip = (uint32_t)((int64_t)t * 64 * ldk * 2);
+    Tile::issue(attn_rsrc(kb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + stage * STAGE, wave, lane, ldk);
+    Tile::issue(attn_rsrc(vb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + stage * STAGE + Tile::BYTES, wave, lane, ldk);
+  };
+
+  issue_tile(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  int stage = 0;
+  for (int t = 0; t < nkv; ++t) {
+    if (t + 1 < nkv) issue_tile(t + 1, stage ^ 1);
+    const int kv0 = t * 64;
+    if (kv0 <= qw + 31) {
+      const char* tk = smem + stage * STAGE;
+      const char* tv = tk + Tile::BYTES;
+      f32x16 s[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[i][e] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < DH / 16; ++kk)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tk, i * 32, kk, lane), qf[kk], s[i], 0, 0, 0);
+      const bool need_mask = kv0 + 63 > qw;
+      const int qi = qw + lq;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float val = s[i][r] * scale_log2;
+          if (need_mask) {
+            const int kvi = kv0 + i * 32 + ((r >> 2) << 3) + (half << 2) + (r & 3);
+            if (kvi > qi) val = -INFINITY;
+          }
+          s[i][r] = val;
+          mx = fmaxf(mx, val);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m, mx);
+      const float alpha = fast_exp2(m - m_new);
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float pv = fast_exp2(s[i][r] - m_new);
+          s[i][r] = pv;
+          psum += pv;
+        }
+      lsum = lsum * alpha + psum;
+      m = m_new;
+#pragma unroll
+      for (int t2 = 0; t2 < DH / 32; ++t2)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[t2][e] *= alpha;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8 pf = pack_slots(s[ks >> 1], (ks & 1) * 8);
+#pragma unroll
+        for (int t2 = 0; t2 < DH / 32; ++t2)
+          oacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tv, t2 * 32, ks * 16, lane), pf, oacc[t2], 0, 0, 0);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    stage ^= 1;
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  const float inv = 1.0f / lsum;
+  bf16_t* op = o + ((int64_t)b * S + qw + lq) * ldq + (int64_t)h * DH + half * 4;
+#pragma unroll
+  for (int t2 = 0; t2 < DH / 32; ++t2)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 ov;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(oacc[t2][g * 4 + e] * inv);
+      *reinterpret_cast<bf16x4*>(op + t2 * 32 + g * 8) = ov;
+    }
+  if (half == 0) lse[((int64_t)b * Hq + h) * S + qw + lq] = (m + log2f(lsum)) * kLn2;
+}
+
+// ------------------------------------------------------------------------------------------
+// delta[b, h, q] = sum_d dO[q, h, d] * O[q, h, d]
+// ------------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restrict__ o,
+                                                         const bf16_t* __restrict__ d_o,
+                                                         float* __restrict__ delta, int64_t rows,
+                                                         int S, int Hq) {
+  constexpr int LPR = DH / 8;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = idx / LPR;  // row = (b*S + q)*Hq + h
+  float acc = 0.f;
+  if (row < rows) {
+    const bf16x8 a = reinterpret_cast<const bf16x8*>(o)[idx], d = reinterpret_cast<const bf16x8*>(d_o)[idx];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)d[e];
+  }
+#pragma unroll
+  for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  if (row < rows && (idx % LPR) == 0) {
+    const int64_t tok = row / Hq;
+    const int h = (int)(row % Hq);
+    const int64_t b = tok / S, qi = tok % S;
+    delta[(b * Hq + h) * S + qi] = acc;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// dQ.  Same decomposition as the forward: workgroup = 128 query rows of one (batch, head).
+// ------------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16_t* __restrict__ dq, int S, int Hq, int Hkv, float scale) {
+  using Tile = RowTile<64, DH, 4>;
+  constexpr int STAGE = 2 * Tile::BYTES;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int hk = h / (Hq / Hkv);
+  const int q0 = qt * 128, qw = q0 + wave * 32;
+  const int lq = lane & 31, half = lane >> 5;
+  const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
+  const float scale_log2 = scale * kLog2e;
+
+  bf16x8 qf[DH / 16], dof[DH / 16];
+  {
+    const int64_t off = ((int64_t)b * S + qw + lq) * ldq + (int64_t)h * DH + half * 8;
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk) {
+      qf[kk] = *reinterpret_cast<const bf16x8*>(q + off + kk * 16);
+      dof[kk] = *reinterpret_cast<const bf16x8*>(d_o + off + kk * 16);
+    }
+  }
+  const int64_t stat = ((int64_t)b * Hq + h) * S + qw + lq;
+  const float lse2 = lse[stat] * kLog2e, dl = delta[stat];
+  f32x16 acc[DH / 32];
+#pragma unroll
+  for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+
+  const bf16_t* kb = k + (int64_t)b * S * ldk + (int64_t)hk * DH;
+  const bf16_t* vb = v + (int64_t)b * S * ldk + (int64_t)hk * DH;
+  const uint32_t kv_bytes = (uint32_t)((((int64_t)S - 1) * ldk + DH) * 2);
+  const int nkv = (q0 + 128) / 64;
+  auto issue_tile = [&](int t, int stage) {
+    const uint32_t skip = (uint32_t)((int64_t)t * 64 * ldk * 2);
+    Tile::issue(attn_rsrc(kb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + stage * STAGE, wave, lane, ldk);
+    Tile::issue(attn_rsrc(vb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + stage * STAGE + Tile::BYTES, wave, lane, ldk);
+  };
+  issue_tile(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  int stage = 0;
+  for (int t = 0; t < nkv; ++t) {
+    if (t + 1 < nkv) issue_tile(t + 1, stage ^ 1);
+    const int kv0 = t * 64;
+    if (kv0 <= qw + 31) {
+      const char* tk = smem + stage * STAGE;
+      const char* tv = tk + Tile::BYTES;
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[i][e] = 0.f; dp[i][e] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < DH / 16; ++kk)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tk, i * 32, kk, lane), qf[kk], s[i], 0, 0, 0);
+          dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tv, i * 32, kk, lane), dof[kk], dp[i], 0, 0, 0);
+        }
+      const bool need_mask = kv0 + 63 > qw;
+      const int qi = qw + lq;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float pv = fast_exp2(s[i][r] * scale_log2 - lse2);
+          if (need_mask) {
+            const int kvi = kv0 + i * 32 + ((r >> 2) << 3) + (half << 2) + (r & 3);
+            if (kvi > qi) pv = 0.f;
+          }
+          s[i][r] = pv * (dp[i][r] - dl);  // dS^T
+        }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8 df = pack_slots(s[ks >> 1], (ks & 1) * 8);
+#pragma unroll
+        for (int t2 = 0; t2 < DH / 32; ++t2)
+          acc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tk, t2 * 32, ks * 16, lane), df, acc[t2], 0, 0, 0);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    stage ^= 1;
+  }
+  bf16_t* op = dq + ((int64_t)b * S + qw + lq) * ldq + (int64_t)h * DH + half * 4;
+#pragma unroll
+  for (int t2 = 0; t2 < DH / 32; ++t2)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 ov;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(acc[t2][g * 4 + e] * scale);
+      *reinterpret_cast<bf16x4*>(op + t2 * 32 + g * 8) = ov;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// dK, dV.  Workgroup = 4 waves = 128 keys of one (batch, kv head); wave = 32 keys.  Streams the
+// Q and dO tiles (64 query rows) of every query head of the group from the diagonal downwards.
+// ------------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
+    bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int S, int Hq, int Hkv, float scale) {
+  using Tile = RowTile<64, DH, 4>;
+  constexpr int STAGE = 2 * Tile::BYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int kt = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int G = Hq / Hkv;
+  const int kv0 = kt * 128, kvw = kv0 + wave * 32;
+  const int lk = lane & 31, half = lane >> 5;
+  const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
+  const float scale_log2 = scale * kLog2e;
+
+  bf16x8 kf[DH / 16], vf[DH / 16];
+  {
+    const int64_t off = ((int64_t)b * S + kvw + lk) * ldk + (int64_t)hk * DH + half * 8;
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk) {
+      kf[kk] = *reinterpret_cast<const bf16x8*>(k + off + kk * 16);
+      vf[kk] = *reinterpret_cast<const bf16x8*>(v + off + kk * 16);
+    }
+  }
+  f32x16 dva[DH / 32], dka[DH / 32];
+#pragma unroll
+  for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dva[t][e] = 0.f; dka[t][e] = 0.f; }
+
+  const int first_qt = kv0 / 64, nq = S / 64 - first_qt, niter = G * nq;
+  const uint32_t q_bytes = (uint32_t)((((int64_t)S - 1) * ldq + DH) * 2);
+  auto issue_tile = [&](int it, int stage) {
+    const int h = hk * G + it / nq, qrow = (first_qt + it % nq) * 64;
+    const int64_t base = ((int64_t)b * S) * ldq + (int64_t)h * DH;
+    const uint32_t skip = (uint32_t)((int64_t)qrow * ldq * 2);
+    char* st = smem + stage * STAGE;
+    Tile::issue(attn_rsrc(q + base + (int64_t)qrow * ldq, q_bytes - skip), st, wave, lane, ldq);
+    Tile::issue(attn_rsrc(d_o + base + (int64_t)qrow * ldq, q_bytes - skip), st + Tile::BYTES, wave, lane, ldq);
+    if (wave == 0) {
+      const int64_t sidx = ((int64_t)b * Hq + h) * S + qrow + lane;
+      float* stat = reinterpret_cast<float*>(st + 2 * Tile::BYTES);
+      stat[lane] = lse[sidx] * kLog2e;
+      stat[64 + lane] = delta[sidx];
+    }
+  };
+  issue_tile(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  int stage = 0;
+  for (int it = 0; it < niter; ++it) {
+    if (it + 1 < niter) issue_tile(it + 1, stage ^ 1);
+    const int qrow = (first_qt + it % nq) * 64;
+    const char* tq = smem + stage * STAGE;
+    const char* tdo = tq + Tile::BYTES;
+    const float* stat = reinterpret_cast<const float*>(tq + 2 * Tile::BYTES);
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+      const int qb = qrow + qs * 32;
+      if (qb + 31 >= kvw) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+        for (int kk = 0; kk < DH / 16; ++kk) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tq, qs * 32, kk, lane), kf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tdo, qs * 32, kk, lane), vf[kk], dp, 0, 0, 0);
+        }
+        const bool need_mask = qb < kvw + 31;
+        const int kvi = kvw + lk;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int ql = qs * 32 + g * 8 + half * 4;
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + ql);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 64 + ql);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = g * 4 + e;
+            float pv = fast_exp2(s[r] * scale_log2 - l4[e]);
+            if (need_mask && kvi > qrow + ql + e) pv = 0.f;
+            s[r] = pv;
+            dp[r] = pv * (dp[r] - d4[e]);
+          }
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          const bf16x8 pf = pack_slots(s, ks * 8), df = pack_slots(dp, ks * 8);
+#pragma unroll
+          for (int t2 = 0; t2 < DH / 32; ++t2) {
+            dva[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tdo, t2 * 32, qs * 32 + ks * 16, lane), pf, dva[t2], 0, 0, 0);
+            dka[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tq, t2 * 32, qs * 32 + ks * 16, lane), df, dka[t2], 0, 0, 0);
+          }
+        }
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    stage ^= 1;
+  }
+  const int64_t off = ((int64_t)b * S + kvw + lk) * ldk + (int64_t)hk * DH + half * 4;
+#pragma unroll
+  for (int t2 = 0; t2 < DH / 32; ++t2)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 ok, ov;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        ok[e] = (bf16_t)(dka[t2][g * 4 + e] * scale);
+        ov[e] = (bf16_t)dva[t2][g * 4 + e];
+      }
+      *reinterpret_cast<bf16x4*>(dk + off + t2 * 32 + g * 8) = ok;
+      *reinterpret_cast<bf16x4*>(dv + off + t2 * 32 + g * 8) = ov;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+template <typename K>
+static int set_lds(K kern, size_t bytes) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return fail(-3, "attention: cannot reserve %zu B of LDS: %s", bytes, hipGetErrorString(e));
+  return 0;
+}
+
+template <int DH>
+static int fwd_dh(const void* q, const void* k, const void* v, int64_t B, int64_t S, int64_t Hq,
+                  int64_t Hkv, void* o, float* lse, hipStream_t st) {
+  const size_t lds = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
+  static bool once = false;
+  if (!once) { if (int rc = set_lds(attn_fwd_kernel<DH>, lds)) return rc; once = true; }
+  const float scale_log2 = (float)(1.0 / sqrt((double)DH)) * kLog2e;
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((unsigned)(S / 128), (unsigned)Hq, (unsigned)B), dim3(256),
+                     lds, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse, (int)S,
+                     (int)Hq, (int)Hkv, scale_log2);
+  return check_launch("attention_forward");
+}
+
+int launch_attention_fwd(const void* q, const void* k, const void* v, int64_t B, int64_t S, int64_t Hq,
+                         int64_t Hkv, int64_t dh, void* o, float* lse, hipStream_t st) {
+  if (dh == 128) return fwd_dh<128>(q, k, v, B, S, Hq, Hkv, o, lse, st);
+  if (dh == 64) return fwd_dh<64>(q, k, v, B, S, Hq, Hkv, o, lse, st);
+  return fwd_dh<32>(q, k, v, B, S, Hq, Hkv, o, lse, st);
+}
+
+size_t attention_bwd_workspace(int64_t B, int64_t S, int64_t Hq, int64_t, int64_t) {
+  return (size_t)B * Hq * S * sizeof(float);
+}
+
+template <int DH>
+static int bwd_dh(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                  const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, void* dq, void* dk,
+                  void* dv, void* workspace, hipStream_t st) {
+  float* delta = (float*)workspace;
+  const int64_t rows = B * S * Hq;
+  const int64_t nthreads = rows * (DH / 8);
+  hipLaunchKernelGGL(attn_delta_kernel<DH>, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, st,
+                     (const bf16_t*)o, (const bf16_t*)d_o, delta, rows, (int)S, (int)Hq);
+  if (int rc = check_launch("attention_backward(delta)")) return rc;
+  const float scale = (float)(1.0 / sqrt((double)DH));
+  const size_t lds_dq = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
+  const size_t lds_kv = 2 * (2 * (size_t)RowTile<64, DH, 4>::BYTES + 512);
+  static bool once = false;
+  if (!once) {
+    if (int rc = set_lds(attn_bwd_dq_kernel<DH>, lds_dq)) return rc;
+    if (int rc = set_lds(attn_bwd_dkdv_kernel<DH>, lds_kv)) return rc;
+    once = true;
+  }
+  hipLaunchKernelGGL(attn_bwd_dkdv_kernel<DH>, dim3((unsigned)(S / 128), (unsigned)Hkv, (unsigned)B), dim3(256),
+                     lds_kv, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)d_o, lse,
+                     (const float*)delta, (bf16_t*)dk, (bf16_t*)dv, (int)S, (int)Hq, (int)Hkv, scale);
+  if (int rc = check_launch("attention_backward(dk,dv)")) return rc;
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3((unsigned)(S / 128), (unsigned)Hq, (unsigned)B), dim3(256),
+                     lds_dq, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)d_o, lse,
+                     (const float*)delta, (bf16_t*)dq, (int)S, (int)Hq, (int)Hkv, scale);
+  return check_launch("attention_backward(dq)");
+}
+
+int launch_attention_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                         const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t dh,
+                         void* dq, void* dk, void* dv, void* workspace, hipStream_t st) {
+  if (dh == 128) return bwd_dh<128>(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dq, dk, dv, workspace, st);
+  if (dh == 64) return bwd_dh<64>(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dq, dk, dv, workspace, st);
+  return bwd_dh<32>(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dq, dk, dv, workspace, st);
+}
+
+}  // namespace dl

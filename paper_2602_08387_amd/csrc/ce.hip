@@ -1,0 +1,145 @@
+// Fused softmax cross-entropy forward + backward over rows of bf16 logits.
+// One 1024-thread workgroup per row.  For V <= 131072 the row is read from HBM once and kept in
+// registers (16 x 8 bf16 per thread) between the max/sum reductions and the gradient write, so
+// the kernel moves 2 bytes in + 2 bytes out per logit; longer rows are re-read.
+#include "common.h"
+#include "kernels.h"
+
+namespace dl {
+
+constexpr int kCeThreads = 1024;
+
+__device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  v = is_max ? wave_max(v) : wave_sum(v);
+  __syncthreads();  // protect red[] from the previous use
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < kCeThreads / 64; ++w) r = is_max ? fmaxf(r, red[w]) : r + red[w];
+  return r;
+}
+
+template <bool CACHED>
+__global__ __launch_bounds__(kCeThreads) void ce_kernel(const bf16_t* logits,
+                                                        const int64_t* __restrict__ targets,
+                                                        int64_t V, float scale,
+                                                        float* __restrict__ row_loss,
+                                                        bf16_t* dlogits) {
+  __shared__ float red[kCeThreads / 64];
+  __shared__ float picked_s;
+  constexpr int NV = 16;
+  const int64_t row = blockIdx.x;
+  const int nvec = (int)(V >> 3);
+  const bf16x8* in = reinterpret_cast<const bf16x8*>(logits + row * V);
+  bf16x8* out = reinterpret_cast<bf16x8*>(dlogits + row * V);
+  const int64_t tgt = targets[row];
+  const bool tgt_ok = tgt >= 0 && tgt < V;
+  if (threadIdx.x == 0) picked_s = tgt_ok ? (float)logits[row * V + tgt] : 0.f;
+
+  bf16x8 v[CACHED ? NV : 1];
+  float mx = -INFINITY;
+  if constexpr (CACHED) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = i * kCeThreads + threadIdx.x;
+      if (c < nvec) {
+        v[i] = in[c];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mx = fmaxf(mx, (float)v[i][e]);
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < nvec; c += kCeThreads) {
+      bf16x8 t = in[c];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) mx = fmaxf(mx, (float)t[e]);
+    }
+  }
+  mx = block_reduce(mx, true, red);
+  float sum = 0.f;
+  if constexpr (CACHED) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = i * kCeThreads + threadIdx.x;
+      if (c < nvec) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum += __expf((float)v[i][e] - mx);
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < nvec; c += kCeThreads) {
+      bf16x8 t = in[c];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += __expf((float)t[e] - mx);
+    }
+  }
+  sum = block_reduce(sum, false, red);  // its barriers also order every read before any write
+  const float lse = mx + __logf(sum);
+  if (threadIdx.x == 0) row_loss[row] = tgt_ok ? lse - picked_s : lse;
+  const int tc = tgt_ok ? (int)(tgt >> 3) : -1, te = (int)(tgt & 7);
+  if constexpr (CACHED) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = i * kCeThreads + threadIdx.x;
+      if (c < nvec) {
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float pr = __expf((float)v[i][e] - lse);
+          if (c == tc && e == te) pr -= 1.0f;
+          o[e] = (bf16_t)(pr * scale);
+        }
+        out[c] = o;
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < nvec; c += kCeThreads) {
+      bf16x8 t = in[c], o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float pr = __expf((float)t[e] - lse);
+        if (c == tc && e == te) pr -= 1.0f;
+        o[e] = (bf16_t)(pr * scale);
+      }
+      out[c] = o;
+    }
+  }
+}
+
+// Mean of the per-row losses, summed in a fixed order by one workgroup.
+__global__ __launch_bounds__(1024) void mean_kernel(const float* __restrict__ v, int64_t n,
+                                                    float* out) {
+  __shared__ float red[16];
+  float s = 0.f;
+  for (int64_t i = threadIdx.x; i < n; i += 1024) s += v[i];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int w = 0; w < 16; ++w) t += red[w];
+    *out = t / (float)n;
+  }
+}
+
+size_t ce_workspace(int64_t T, int64_t) { return (size_t)T * sizeof(float); }
+
+int launch_ce(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
+              float* loss, void* dlogits, void* workspace, hipStream_t st) {
+  const float scale = grad_scale / (float)T;
+  float* row_loss = (float*)workspace;
+  if (V <= (int64_t)kCeThreads * 8 * 16)
+    hipLaunchKernelGGL(ce_kernel<true>, dim3((unsigned)T), dim3(kCeThreads), 0, st,
+                       (const bf16_t*)logits, targets, V, scale, row_loss, (bf16_t*)dlogits);
+  else
+    hipLaunchKernelGGL(ce_kernel<false>, dim3((unsigned)T), dim3(kCeThreads), 0, st,
+                       (const bf16_t*)logits, targets, V, scale, row_loss, (bf16_t*)dlogits);
+  int rc = check_launch("ce_loss_fwd_bwd");
+  if (rc) return rc;
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, st, (const float*)row_loss, T, loss);
+  return check_launch("ce_loss_fwd_bwd(mean)");
+}
+
+}  // namespace dl

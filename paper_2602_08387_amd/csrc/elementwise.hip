@@ -1,0 +1,432 @@
+// Memory-bound kernels of the decoder layer: RMSNorm forward/backward, rotary embedding,
+// SwiGLU forward/backward, bf16 matrix transpose, embedding gather and its gradient.
+// All of them move 16 bytes per lane per access (8 bf16) with consecutive lanes on
+// consecutive addresses, keep a row in registers between the reduction and the write, and
+// reduce with wavefront shuffles.
+#include "common.h"
+#include "kernels.h"
+
+namespace dl {
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm forward: one wavefront per token row, the row stays in registers.
+// ------------------------------------------------------------------------------------------
+template <int NV>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const bf16_t* __restrict__ x,
+                                                          const bf16_t* __restrict__ gamma,
+                                                          bf16_t* __restrict__ h,
+                                                          float* __restrict__ rstd, int64_t T,
+                                                          int D, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const int nvec = D >> 3;
+  const bf16x8* xr = reinterpret_cast<const bf16x8*>(x + row * D);
+  bf16x8 v[NV];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = i * 64 + lane;
+    if (c < nvec) {
+      v[i] = xr[c];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { float f = (float)v[i][e]; ss += f * f; }
+    }
+  }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)D + eps);
+  if (lane == 0) rstd[row] = r;
+  bf16x8* hr = reinterpret_cast<bf16x8*>(h + row * D);
+  const bf16x8* gr = reinterpret_cast<const bf16x8*>(gamma);
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = i * 64 + lane;
+    if (c < nvec) {
+      bf16x8 g = gr[c], o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)v[i][e] * r * (float)g[e]);
+      hr[c] = o;
+    }
+  }
+}
+
+int launch_rmsnorm_fwd(const void* x, const void* gamma, int64_t T, int64_t D, float eps, void* h,
+                       float* rstd, hipStream_t st) {
+  const int nv = (int)((D / 8 + 63) / 64);
+  dim3 grid((unsigned)((T + 3) / 4)), block(256);
+#define RMS_FWD(NV)                                                                             \
+  hipLaunchKernelGGL(rmsnorm_fwd_kernel<NV>, grid, block, 0, st, (const bf16_t*)x,              \
+                     (const bf16_t*)gamma, (bf16_t*)h, rstd, T, (int)D, eps)
+  if (nv <= 1) RMS_FWD(1);
+  else if (nv <= 2) RMS_FWD(2);
+  else if (nv <= 4) RMS_FWD(4);
+  else if (nv <= 8) RMS_FWD(8);
+  else if (nv <= 16) RMS_FWD(16);
+  else RMS_FWD(32);
+#undef RMS_FWD
+  return check_launch("rmsnorm_forward");
+}
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm backward.  Each wavefront walks rows with a grid stride, writes dx for its rows and
+// keeps the gain-gradient partial sums of its columns in registers; the block then folds its
+// waves through LDS and writes one fp32 partial row; a second kernel sums the partial rows.
+// ------------------------------------------------------------------------------------------
+constexpr int kRmsBwdWaves = 8;
+
+template <int NV>
+__global__ __launch_bounds__(64 * kRmsBwdWaves) void rmsnorm_bwd_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma, const float* __restrict__ rstd,
+    const bf16_t* __restrict__ dh, const bf16_t* dres, bf16_t* dx, float* __restrict__ partial,
+    int64_t T, int D) {
+  extern __shared__ float red[];  // [kRmsBwdWaves][D]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nvec = D >> 3;
+  float dg[NV][8];
+  bf16x8 gv[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = i * 64 + lane;
+    if (c < nvec) gv[i] = reinterpret_cast<const bf16x8*>(gamma)[c];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dg[i][e] = 0.f;
+  }
+  const int64_t wstride = (int64_t)gridDim.x * kRmsBwdWaves;
+  for (int64_t row = (int64_t)blockIdx.x * kRmsBwdWaves + wave; row < T; row += wstride) {
+    const bf16x8* xr = reinterpret_cast<const bf16x8*>(x + row * D);
+    const bf16x8* dr = reinterpret_cast<const bf16x8*>(dh + row * D);
+    const float r = rstd[row];
+    bf16x8 xv[NV], dv[NV];
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = i * 64 + lane;
+      if (c < nvec) {
+        xv[i] = xr[c];
+        dv[i] = dr[c];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = (float)xv[i][e] * r, d = (float)dv[i][e];
+          dg[i][e] += d * xh;
+          dot += d * (float)gv[i][e] * xh;
+        }
+      }
+    }
+    dot = wave_sum(dot) / (float)D;
+    bf16x8* oxr = reinterpret_cast<bf16x8*>(dx + row * D);
+    const bf16x8* rr = dres ? reinterpret_cast<const bf16x8*>(dres + row * D) : nullptr;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = i * 64 + lane;
+      if (c < nvec) {
+        bf16x8 o, rs;
+        if (rr) rs = rr[c];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = (float)xv[i][e] * r;
+          float g = r * ((float)dv[i][e] * (float)gv[i][e] - xh * dot);
+          if (rr) g += (float)rs[e];
+          o[e] = (bf16_t)g;
+        }
+        oxr[c] = o;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = i * 64 + lane;
+    if (c < nvec) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[wave * D + c * 8 + e] = dg[i][e];
+    }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < D; c += blockDim.x) {
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < kRmsBwdWaves; ++w) s += red[w * D + c];
+    partial[(int64_t)blockIdx.x * D + c] = s;
+  }
+}
+
+__global__ void colsum_partials_kernel(const float* __restrict__ partial, int nrows, int D,
+                                       bf16_t* out, int accumulate) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= D) return;
+  float s = 0.f;
+  for (int r = 0; r < nrows; ++r) s += partial[(int64_t)r * D + c];
+  if (accumulate) s += (float)out[c];
+  out[c] = (bf16_t)s;
+}
+
+static int rms_bwd_blocks(int64_t T) {
+  int64_t b = (T + kRmsBwdWaves - 1) / kRmsBwdWaves;
+  return (int)(b < 512 ? b : 512);
+}
+size_t rmsnorm_bwd_workspace(int64_t T, int64_t D) { return (size_t)rms_bwd_blocks(T) * D * sizeof(float); }
+
+int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, const void* dh,
+                       const void* dres, int64_t T, int64_t D, void* dx, void* dgamma,
+                       int accumulate, void* workspace, hipStream_t st) {
+  const int nv = (int)((D / 8 + 63) / 64);
+  const int nb = rms_bwd_blocks(T);
+  const size_t lds = (size_t)kRmsBwdWaves * D * sizeof(float);
+  dim3 grid(nb), block(64 * kRmsBwdWaves);
+#define RMS_BWD(NV)                                                                             \
+  hipLaunchKernelGGL(rmsnorm_bwd_kernel<NV>, grid, block, lds, st, (const bf16_t*)x,            \
+                     (const bf16_t*)gamma, rstd, (const bf16_t*)dh, (const bf16_t*)dres,        \
+                     (bf16_t*)dx, (float*)workspace, T, (int)D)
+  if (nv <= 1) RMS_BWD(1);
+  else if (nv <= 2) RMS_BWD(2);
+  else if (nv <= 4) RMS_BWD(4);
+  else if (nv <= 8) RMS_BWD(8);
+  else return fail(-1, "rmsnorm_backward: D=%lld above 4096 is not supported", (long long)D);
+#undef RMS_BWD
+  int rc = check_launch("rmsnorm_backward");
+  if (rc) return rc;
+  hipLaunchKernelGGL(colsum_partials_kernel, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st,
+                     (const float*)workspace, nb, (int)D, (bf16_t*)dgamma, accumulate);
+  return check_launch("rmsnorm_backward(dgamma)");
+}
+
+// ------------------------------------------------------------------------------------------
+// Rotary embedding, in place.  One block per token: the first head_dim/2 threads evaluate the
+// angle p * base^(-2i/dh) and its sine/cosine in fp64 (positions reach 8191 rad, where fp32
+// range reduction is not accurate enough), park them in LDS as fp32, then every thread rotates
+// pairs of all heads of that token.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rope_kernel(bf16_t* z, int seq, int n_heads, int head_dim,
+                                                   double log2_base, int layout, int inverse) {
+  __shared__ float cs[64], sn[64];
+  const int64_t tok = blockIdx.x;
+  const int p = (int)(tok % seq);
+  const int half = head_dim >> 1;
+  if ((int)threadIdx.x < half) {
+    const double theta = exp2(-2.0 * (double)threadIdx.x / (double)head_dim * log2_base);
+    double s, c;
+    sincos((double)p * theta, &s, &c);
+    cs[threadIdx.x] = (float)c;
+    sn[threadIdx.x] = inverse ? -(float)s : (float)s;
+  }
+  __syncthreads();
+  bf16_t* zt = z + tok * (int64_t)n_heads * head_dim;
+  if (layout == 0) {
+    // pairs (i, i + half): handle 8 consecutive i per thread
+    const int groups = half >> 3;  // per head
+    for (int w = threadIdx.x; w < n_heads * groups; w += blockDim.x) {
+      const int hd = w / groups, i0 = (w % groups) << 3;
+      bf16x8* pa = reinterpret_cast<bf16x8*>(zt + hd * head_dim + i0);
+      bf16x8* pb = reinterpret_cast<bf16x8*>(zt + hd * head_dim + half + i0);
+      bf16x8 a = *pa, b = *pb, oa, ob;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float c = cs[i0 + e], s = sn[i0 + e], fa = (float)a[e], fb = (float)b[e];
+        oa[e] = (bf16_t)(fa * c - fb * s);
+        ob[e] = (bf16_t)(fa * s + fb * c);
+      }
+      *pa = oa;
+      *pb = ob;
+    }
+  } else {
+    const int groups = head_dim >> 3;
+    for (int w = threadIdx.x; w < n_heads * groups; w += blockDim.x) {
+      const int hd = w / groups, e0 = (w % groups) << 3;
+      bf16x8* pz = reinterpret_cast<bf16x8*>(zt + hd * head_dim + e0);
+      bf16x8 v = *pz, o;
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        const int i = (e0 + e) >> 1;
+        const float c = cs[i], s = sn[i], fa = (float)v[e], fb = (float)v[e + 1];
+        o[e] = (bf16_t)(fa * c - fb * s);
+        o[e + 1] = (bf16_t)(fa * s + fb * c);
+      }
+      *pz = o;
+    }
+  }
+}
+
+int launch_rope(void* z, int64_t batch, int64_t seq, int64_t n_heads, int64_t head_dim,
+                float base, int layout, int inverse, hipStream_t st) {
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)(batch * seq)), dim3(256), 0, st, (bf16_t*)z,
+                     (int)seq, (int)n_heads, (int)head_dim, log2((double)base), layout, inverse);
+  return check_launch("rope_apply");
+}
+
+// ------------------------------------------------------------------------------------------
+// SwiGLU
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const bf16x8* __restrict__ g,
+                                                         const bf16x8* __restrict__ u,
+                                                         bf16x8* __restrict__ a, int64_t nvec) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    bf16x8 gv = g[i], uv = u[i], o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float z = (float)gv[e];
+      o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * (float)uv[e]);
+    }
+    a[i] = o;
+  }
+}
+
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16x8* g, const bf16x8* u,
+                                                         const bf16x8* __restrict__ da, bf16x8* dg,
+                                                         bf16x8* du, int64_t nvec) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    bf16x8 gv = g[i], uv = u[i], dv = da[i], og, ou;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float z = (float)gv[e], d = (float)dv[e];
+      const float s = 1.0f / (1.0f + __expf(-z));
+      og[e] = (bf16_t)(d * (float)uv[e] * s * (1.0f + z * (1.0f - s)));
+      ou[e] = (bf16_t)(d * z * s);
+    }
+    dg[i] = og;
+    du[i] = ou;
+  }
+}
+
+static unsigned ew_blocks(int64_t nvec) {
+  int64_t b = (nvec + 255) / 256;
+  return (unsigned)(b < 256 * 16 ? (b > 0 ? b : 1) : 256 * 16);
+}
+
+int launch_swiglu_fwd(const void* g, const void* u, int64_t n, void* a, hipStream_t st) {
+  hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(ew_blocks(n / 8)), dim3(256), 0, st, (const bf16x8*)g,
+                     (const bf16x8*)u, (bf16x8*)a, n / 8);
+  return check_launch("swiglu_forward");
+}
+int launch_swiglu_bwd(const void* g, const void* u, const void* da, int64_t n, void* dg, void* du,
+                      hipStream_t st) {
+  hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(ew_blocks(n / 8)), dim3(256), 0, st, (const bf16x8*)g,
+                     (const bf16x8*)u, (const bf16x8*)da, (bf16x8*)dg, (bf16x8*)du, n / 8);
+  return check_launch("swiglu_backward");
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 transpose: out[c][r] = in[r][c], 64x64 tiles through LDS (16-byte global accesses on
+// both sides).  R and C are multiples of 64.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_kernel(const bf16_t* __restrict__ in,
+                                                        bf16_t* __restrict__ out, int64_t R,
+                                                        int64_t C) {
+  __shared__ bf16_t tile[64][66];
+  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int idx = it * 256 + t;         // 512 vectors of 8
+    const int r = idx >> 3, cv = (idx & 7) << 3;
+    bf16x8 v = *reinterpret_cast<const bf16x8*>(in + (r0 + r) * C + c0 + cv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tile[r][cv + e] = v[e];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int idx = it * 256 + t;
+    const int c = idx >> 3, rv = (idx & 7) << 3;
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = tile[rv + e][c];
+    *reinterpret_cast<bf16x8*>(out + (c0 + c) * R + r0 + rv) = v;
+  }
+}
+
+int launch_transpose(const void* in, void* out, int64_t R, int64_t C, hipStream_t st) {
+  hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)(C / 64), (unsigned)(R / 64)), dim3(256), 0,
+                     st, (const bf16_t*)in, (bf16_t*)out, R, C);
+  return check_launch("transpose");
+}
+
+// ------------------------------------------------------------------------------------------
+// Embedding gather and its gradient.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void embed_fwd_kernel(const bf16_t* __restrict__ table,
+                                                        const int64_t* __restrict__ ids,
+                                                        bf16_t* __restrict__ x0, int64_t V, int D) {
+  const int64_t t = blockIdx.x;
+  int64_t id = ids[t];
+  const bool ok = id >= 0 && id < V;
+  const bf16x8* src = reinterpret_cast<const bf16x8*>(table + (ok ? id : 0) * D);
+  bf16x8* dst = reinterpret_cast<bf16x8*>(x0 + t * D);
+  bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int c = threadIdx.x; c < (D >> 3); c += blockDim.x) dst[c] = ok ? src[c] : zero;
+}
+
+int launch_embed_fwd(const void* table, const int64_t* ids, int64_t T, int64_t V, int64_t D,
+                     void* x0, hipStream_t st) {
+  hipLaunchKernelGGL(embed_fwd_kernel, dim3((unsigned)T), dim3(256), 0, st, (const bf16_t*)table,
+                     ids, (bf16_t*)x0, V, (int)D);
+  return check_launch("embed_forward");
+}
+
+__global__ __launch_bounds__(256) void zero_kernel(u32x4* p, int64_t nvec) {
+  const u32x4 z = {0, 0, 0, 0};
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec;
+       i += (int64_t)gridDim.x * blockDim.x)
+    p[i] = z;
+}
+
+// One block per token t.  The block scans all ids; it owns row ids[t] iff no earlier token has
+// the same id, and then sums (fp32, token order) the gradient rows of every token with that id.
+__global__ __launch_bounds__(256) void embed_bwd_kernel(const bf16_t* __restrict__ dx0,
+                                                        const int64_t* __restrict__ ids,
+                                                        bf16_t* __restrict__ dtable, int64_t T,
+                                                        int64_t V, int D) {
+  __shared__ int earlier;
+  __shared__ int match[1024];
+  const int64_t t = blockIdx.x;
+  const int64_t id = ids[t];
+  if (id < 0 || id >= V) return;  // uniform over the block
+  if (threadIdx.x == 0) earlier = 0;
+  __syncthreads();
+  for (int64_t s = threadIdx.x; s < t; s += blockDim.x)
+    if (ids[s] == id) earlier = 1;
+  __syncthreads();
+  if (earlier) return;            // uniform over the block
+  const int nv = D >> 3;
+  bf16x8* out = reinterpret_cast<bf16x8*>(dtable + id * D);
+  for (int c0 = 0; c0 < nv; c0 += blockDim.x) {
+    const int c = c0 + threadIdx.x;
+    float a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int64_t base = t; base < T; base += 1024) {
+      __syncthreads();
+      for (int k = threadIdx.x; k < 1024; k += blockDim.x) {
+        const int64_t s = base + k;
+        match[k] = (s < T && ids[s] == id) ? 1 : 0;
+      }
+      __syncthreads();
+      if (c < nv) {
+        for (int k = 0; k < 1024; ++k) {
+          if (match[k]) {
+            bf16x8 v = reinterpret_cast<const bf16x8*>(dx0 + (base + k) * D)[c];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a[e] += (float)v[e];
+          }
+        }
+      }
+    }
+    if (c < nv) {
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)a[e];
+      out[c] = o;
+    }
+  }
+}
+
+int launch_embed_bwd(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D,
+                     void* dtable, hipStream_t st) {
+  const int64_t nvec = V * D / 8;
+  hipLaunchKernelGGL(zero_kernel, dim3(ew_blocks(nvec)), dim3(256), 0, st, (u32x4*)dtable, nvec);
+  int rc = check_launch("embed_backward(zero)");
+  if (rc) return rc;
+  hipLaunchKernelGGL(embed_bwd_kernel, dim3((unsigned)T), dim3(256), 0, st, (const bf16_t*)dx0, ids,
+                     (bf16_t*)dtable, T, V, (int)D);
+  return check_launch("embed_backward");
+}
+
+}  // namespace dl

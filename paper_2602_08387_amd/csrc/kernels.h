@@ -1,0 +1,65 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernel files.
+// Every launcher validates nothing (the C-ABI layer did), enqueues on `st` and returns 0 or a
+// DLAYER_ERR_LAUNCH code with the thread-local message set.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dl {
+
+// ---- elementwise.hip
+int launch_rmsnorm_fwd(const void* x, const void* gamma, int64_t T, int64_t D, float eps, void* h,
+                       float* rstd, hipStream_t st);
+size_t rmsnorm_bwd_workspace(int64_t T, int64_t D);
+int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, const void* dh,
+                       const void* dres, int64_t T, int64_t D, void* dx, void* dgamma,
+                       int accumulate, void* workspace, hipStream_t st);
+int launch_rope(void* z, int64_t batch, int64_t seq, int64_t n_heads, int64_t head_dim, float base,
+                int layout, int inverse, hipStream_t st);
+int launch_swiglu_fwd(const void* g, const void* u, int64_t n, void* a, hipStream_t st);
+int launch_swiglu_bwd(const void* g, const void* u, const void* da, int64_t n, void* dg, void* du,
+                      hipStream_t st);
+int launch_transpose(const void* in, void* out, int64_t R, int64_t C, hipStream_t st);
+int launch_embed_fwd(const void* table, const int64_t* ids, int64_t T, int64_t V, int64_t D,
+                     void* x0, hipStream_t st);
+int launch_embed_bwd(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D,
+                     void* dtable, hipStream_t st);
+
+// ---- gemm.hip
+// C[M,N] (bf16, row-major, leading dimension ldc) = sum over segments s of opA_s * opB_s
+//        (+ R[M,N] if R) (+ C if accumulate), fp32 accumulation.
+// Segment operands are bf16 row-major.  a_kmajor: A_s is [M, K_s] (lda >= K_s) else [K_s, M]
+// (lda >= M).  b_kmajor: B_s is [N, K_s] else [K_s, N].  K_s % 64 == 0, N % 8 == 0.
+struct GemmSeg {
+  const void* a;
+  const void* b;
+  int64_t lda, ldb;
+  int K;
+};
+struct GemmArgs {
+  GemmSeg seg[3];
+  int nseg;
+  int M, N;
+  void* c;
+  int64_t ldc;
+  const void* r;  // optional residual, same leading dimension as c
+  int accumulate;
+  bool a_kmajor, b_kmajor;
+};
+int launch_gemm(const GemmArgs& g, hipStream_t st);
+
+// ---- attention.hip
+int launch_attention_fwd(const void* q, const void* k, const void* v, int64_t B, int64_t S,
+                         int64_t Hq, int64_t Hkv, int64_t dh, void* o, float* lse, hipStream_t st);
+size_t attention_bwd_workspace(int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t dh);
+int launch_attention_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                         const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t dh,
+                         void* dq, void* dk, void* dv, void* workspace, hipStream_t st);
+
+// ---- ce.hip
+size_t ce_workspace(int64_t T, int64_t V);
+int launch_ce(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
+              float* loss, void* dlogits, void* workspace, hipStream_t st);
+
+}  // namespace dl

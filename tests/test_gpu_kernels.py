@@ -1,0 +1,244 @@
+"""Step-by-step GPU parity: every building block of the layer, called through the C ABI, against
+the fp64 oracle on the same seeded bf16 inputs.  Sizes span several tiles and ragged tails."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder_layer as odl
+from oracle import lm_stack as olm
+from synth import inputs as si
+from tests.parity import (assert_close, cosine, dev_bf16, dev_from_f64, host_f64, rel_err, rounded)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def K():
+    import paper_2602_08387_amd as k
+    return k
+
+
+def _rand_bits(rng, shape, std=1.0, mean=0.0):
+    return si.f32_to_bf16_bits((rng.standard_normal(shape) * std + mean).astype(np.float32))
+
+
+def _ws(nbytes):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+# ------------------------------------------------------------------ RMSNorm
+@pytest.mark.parametrize("T,D", [(300, 128), (1024, 768), (77, 2048), (130, 4096)])
+def test_rmsnorm_forward_backward(K, T, D):
+    rng = np.random.default_rng(T + D)
+    xb, gb, db, rb = (_rand_bits(rng, (T, D)), _rand_bits(rng, (D,), 0.02, 1.0),
+                      _rand_bits(rng, (T, D)), _rand_bits(rng, (T, D)))
+    xb = xb.copy()
+    x32 = si.bf16_bits_to_f32(xb)
+    x32[1] *= 1e4      # one huge row, one tiny row
+    x32[2] *= 1e-4
+    xb = si.f32_to_bf16_bits(x32)
+    x, g, dh, dres = map(si.bf16_bits_to_f64, (xb, gb, db, rb))
+    eps = 1e-5
+    h_ref, rstd_ref = odl.rmsnorm_fwd(x, g, eps)
+    dx_ref, dg_ref = odl.rmsnorm_bwd(x, g, rstd_ref, dh)
+    xd, gd, dhd, dresd = map(dev_bf16, (xb, gb, db, rb))
+    h = torch.empty_like(xd)
+    rstd = torch.empty(T, dtype=torch.float32, device="cuda")
+    K.rmsnorm_forward(xd, gd, T, D, eps, h, rstd)
+    assert_close(h, h_ref, "h", rel_tol=1e-2)
+    assert_close(rstd, rstd_ref, "rstd", rel_tol=1e-5)
+    dx = torch.empty_like(xd)
+    dgam = torch.empty(D, dtype=torch.bfloat16, device="cuda")
+    ws = _ws(K.rmsnorm_backward_workspace_bytes(T, D))
+    K.rmsnorm_backward(xd, gd, rstd, dhd, None, T, D, dx, dgam, 0, ws)
+    assert_close(dx, dx_ref, "dx", rel_tol=1e-2)
+    assert_close(dgam, dg_ref, "dgamma", rel_tol=1e-2)
+    # with a residual gradient, in place over dres, accumulating dgamma
+    K.rmsnorm_backward(xd, gd, rstd, dhd, dresd, T, D, dresd, dgam, 1, ws)
+    assert_close(dresd, dx_ref + dres, "dx+dres", rel_tol=1e-2)
+    assert_close(dgam, 2 * dg_ref, "dgamma accumulated", rel_tol=1.5e-2)
+
+
+# ------------------------------------------------------------------ RoPE
+@pytest.mark.parametrize("B,S,H,dh,base,layout", [
+    (2, 128, 4, 32, 1e4, 0), (1, 384, 3, 64, 1e4, 1), (1, 8192, 2, 128, 5e5, 0), (1, 2048, 2, 128, 1e4, 1)])
+def test_rope(K, B, S, H, dh, base, layout):
+    rng = np.random.default_rng(S + dh)
+    zb = _rand_bits(rng, (B, S, H, dh))
+    z = si.bf16_bits_to_f64(zb)
+    phi = odl.rope_angles(S, dh, base)
+    ref = odl.rope_rotate(z, phi, layout)
+    zd = dev_bf16(zb)
+    K.rope_apply(zd, B, S, H, dh, base, layout, 0)
+    assert_close(zd, ref, "rope", rel_tol=6e-3)
+    # inverse rotation of the (bf16-rounded) result
+    got = host_f64(zd)
+    K.rope_apply(zd, B, S, H, dh, base, layout, 1)
+    assert_close(zd, odl.rope_rotate(got, phi, layout, inverse=True), "rope inverse", rel_tol=6e-3)
+
+
+# ------------------------------------------------------------------ SwiGLU
+def test_swiglu(K):
+    rng = np.random.default_rng(5)
+    n = 8 * 12345
+    gb, ub, db = _rand_bits(rng, n, 3.0), _rand_bits(rng, n), _rand_bits(rng, n)
+    g, u, da = map(si.bf16_bits_to_f64, (gb, ub, db))
+    gd, ud, dd = map(dev_bf16, (gb, ub, db))
+    a = torch.empty_like(gd)
+    K.swiglu_forward(gd, ud, n, a)
+    assert_close(a, odl.swiglu_fwd(g, u), "a", rel_tol=6e-3)
+    dg_ref, du_ref = odl.swiglu_bwd(g, u, da)
+    du = torch.empty_like(gd)
+    K.swiglu_backward(gd, ud, dd, n, dd, du)   # dg written over da
+    assert_close(dd, dg_ref, "dg", rel_tol=6e-3)
+    assert_close(du, du_ref, "du", rel_tol=6e-3)
+
+
+# ------------------------------------------------------------------ linear layers (the MFMA GEMM)
+@pytest.mark.parametrize("T,Kd,N,res", [
+    (128, 128, 128, False), (200, 64, 72, True), (512, 768, 2304, False), (1000, 2048, 1024, True),
+    (2048, 4096, 4096, False), (4096, 1024, 5632, True)])
+def test_linear_forward(K, T, Kd, N, res):
+    rng = np.random.default_rng(T + N)
+    xb, wb, rb = _rand_bits(rng, (T, Kd)), _rand_bits(rng, (N, Kd), 0.05), _rand_bits(rng, (T, N))
+    x, w, r = map(si.bf16_bits_to_f64, (xb, wb, rb))
+    ref = x @ w.T + (r if res else 0.0)
+    xd, wd, rd = map(dev_bf16, (xb, wb, rb))
+    y = torch.full((T, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    K.linear_forward(xd, wd, rd if res else None, T, Kd, N, y)
+    assert_close(y, ref, "y", rel_tol=8e-3)
+    y2 = torch.empty_like(y)
+    K.linear_forward(xd, wd, rd if res else None, T, Kd, N, y2)
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16)), "GEMM is not run-to-run bitwise stable"
+
+
+@pytest.mark.parametrize("T,Kd,N", [(128, 128, 128), (192, 64, 320), (1024, 768, 2048), (2048, 2048, 5632),
+                                     (4096, 4096, 1024)])
+def test_linear_backward(K, T, Kd, N):
+    rng = np.random.default_rng(T + N + 1)
+    xb, wb, db = _rand_bits(rng, (T, Kd)), _rand_bits(rng, (N, Kd), 0.05), _rand_bits(rng, (T, N))
+    x, w, dy = map(si.bf16_bits_to_f64, (xb, wb, db))
+    xd, wd, dd = map(dev_bf16, (xb, wb, db))
+    dx = torch.full((T, Kd), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dw = torch.full((N, Kd), float("nan"), dtype=torch.bfloat16, device="cuda")
+    K.linear_backward(xd, wd, dd, T, Kd, N, dx, dw, 0, None)
+    assert_close(dx, dy @ w, "dx", rel_tol=8e-3)
+    assert_close(dw, dy.T @ x, "dw", rel_tol=8e-3)
+    K.linear_backward(xd, wd, dd, T, Kd, N, None, dw, 1, None)
+    assert_close(dw, 2 * (dy.T @ x), "dw accumulated", rel_tol=1.2e-2)
+
+
+# ------------------------------------------------------------------ attention
+ATTN_CASES = [(2, 128, 4, 4, 32, 1.0), (1, 384, 4, 2, 64, 1.0), (2, 256, 8, 2, 128, 1.0),
+              (1, 512, 4, 1, 128, 4.0), (1, 1024, 2, 2, 64, 1.0)]
+
+
+@pytest.mark.parametrize("B,S,Hq,Hkv,dh,qk_std", ATTN_CASES)
+def test_attention_forward_backward(K, B, S, Hq, Hkv, dh, qk_std):
+    rng = np.random.default_rng(S + dh + Hq)
+    qb, kb = _rand_bits(rng, (B, S, Hq, dh), qk_std), _rand_bits(rng, (B, S, Hkv, dh), qk_std)
+    vb, dob = _rand_bits(rng, (B, S, Hkv, dh)), _rand_bits(rng, (B, S, Hq, dh))
+    q, k, v, do = map(si.bf16_bits_to_f64, (qb, kb, vb, dob))
+    o_ref, lse_ref = odl.attention_fwd(q, k, v)
+    qd, kd, vd, dod = map(dev_bf16, (qb, kb, vb, dob))
+    o = torch.full_like(qd, float("nan"))
+    lse = torch.empty(B, Hq, S, dtype=torch.float32, device="cuda")
+    K.attention_forward(qd, kd, vd, B, S, Hq, Hkv, dh, o, lse)
+    assert_close(o, o_ref, "o", rel_tol=1.5e-2)
+    assert_close(lse, lse_ref, "lse", rel_tol=1e-4)
+    # first row attends to itself only
+    assert torch.equal(o[:, 0].view(torch.int16), vd[:, 0].repeat_interleave(Hq // Hkv, dim=1).view(torch.int16))
+    # backward, fed with the oracle's forward output rounded to bf16
+    od = dev_from_f64(o_ref)
+    dq_ref, dk_ref, dv_ref = odl.attention_bwd(q, k, v, do)
+    dq, dk, dv = torch.full_like(qd, float("nan")), torch.full_like(kd, float("nan")), torch.full_like(vd, float("nan"))
+    ws = _ws(K.attention_backward_workspace_bytes(B, S, Hq, Hkv, dh))
+    K.attention_backward(qd, kd, vd, od, dod, lse, B, S, Hq, Hkv, dh, dq, dk, dv, ws)
+    assert_close(dq, dq_ref, "dq")
+    assert_close(dk, dk_ref, "dk")
+    assert_close(dv, dv_ref, "dv")
+
+
+def test_attention_softmax_rows_sum_to_one(K):
+    """v == 1 everywhere makes every output element the sum of its softmax row."""
+    B, S, Hq, Hkv, dh = 1, 512, 4, 2, 128
+    rng = np.random.default_rng(3)
+    qd, kd = dev_bf16(_rand_bits(rng, (B, S, Hq, dh))), dev_bf16(_rand_bits(rng, (B, S, Hkv, dh)))
+    vd = torch.ones(B, S, Hkv, dh, dtype=torch.bfloat16, device="cuda")
+    o = torch.empty_like(qd)
+    lse = torch.empty(B, Hq, S, dtype=torch.float32, device="cuda")
+    K.attention_forward(qd, kd, vd, B, S, Hq, Hkv, dh, o, lse)
+    assert (o.float() - 1).abs().max().item() <= 2 ** -7
+
+
+# ------------------------------------------------------------------ cross-entropy
+@pytest.mark.parametrize("T,V,alias", [(64, 8000, False), (40, 128256, True), (8, 131080, False)])
+def test_ce_loss(K, T, V, alias):
+    rng = np.random.default_rng(V)
+    lb = _rand_bits(rng, (T, V), 2.0)
+    tg = rng.integers(0, V, T)
+    lg = si.bf16_bits_to_f64(lb)
+    loss_ref, dlg_ref, _ = olm.ce_loss_fwd_bwd(lg, tg, grad_scale=1.0)
+    ld = dev_bf16(lb)
+    td = torch.from_numpy(tg).cuda()
+    out = ld if alias else torch.full_like(ld, float("nan"))
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = _ws(K.ce_loss_workspace_bytes(T, V))
+    K.ce_loss_fwd_bwd(ld, td, T, V, 1.0, loss, out, ws)
+    assert abs(loss.item() - loss_ref) <= 1e-5 * abs(loss_ref)
+    assert_close(out, dlg_ref, "dlogits", rel_tol=1e-2)
+    # the target entries carry the -1
+    got = host_f64(out)
+    idx = np.arange(T)
+    assert np.all(np.abs(got[idx, tg] - dlg_ref[idx, tg]) <= 1e-2 * np.abs(dlg_ref[idx, tg]))
+
+
+def test_ce_zero_logits_gives_log_vocab(K):
+    T, V = 16, si.VOCAB_8B
+    ld = torch.zeros(T, V, dtype=torch.bfloat16, device="cuda")
+    td = torch.arange(T, device="cuda") * 7919
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    K.ce_loss_fwd_bwd(ld, td, T, V, 1.0, loss, ld, _ws(K.ce_loss_workspace_bytes(T, V)))
+    assert abs(loss.item() - 11.7617835456) < 2e-5
+
+
+# ------------------------------------------------------------------ embedding
+def test_embedding_forward_backward(K):
+    rng = np.random.default_rng(9)
+    V, D, T = 1000, 256, 700
+    ids = rng.integers(0, V, T)
+    ids[:50] = 7          # heavy duplicate
+    ids[600:] = ids[100:200]
+    Eb, db = _rand_bits(rng, (V, D), 0.02), _rand_bits(rng, (T, D))
+    Ed, dd, idd = dev_bf16(Eb), dev_bf16(db), torch.from_numpy(ids).cuda()
+    x0 = torch.empty(T, D, dtype=torch.bfloat16, device="cuda")
+    K.embed_forward(Ed, idd, T, V, D, x0)
+    assert torch.equal(x0.view(torch.int16), Ed[idd].view(torch.int16))
+    dE = torch.full((V, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    K.embed_backward(dd, idd, T, V, D, dE)
+    ref = olm.embed_bwd(si.bf16_bits_to_f64(db), ids, V)
+    assert_close(dE, ref, "dE", rel_tol=6e-3)
+    absent = np.setdiff1d(np.arange(V), ids)
+    assert np.all(host_f64(dE)[absent] == 0)
+
+
+# ------------------------------------------------------------------ argument checking (host side only)
+def test_bad_arguments_are_rejected_before_any_launch(K):
+    x = torch.zeros(128, 128, dtype=torch.bfloat16, device="cuda")
+    y = torch.full((128, 128), 3.0, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(K.DLayerError, match="K % 64"):
+        K.linear_forward(x, x, None, 128, 100, 128, y)
+    with pytest.raises(K.DLayerError, match="aligned"):
+        K.linear_forward(x.view(-1)[1:], x, None, 64, 64, 64, y)
+    with pytest.raises(K.DLayerError, match="head_dim"):
+        K.attention_forward(x, x, x, 1, 128, 2, 2, 48, y, torch.zeros(256, device="cuda"))
+    with pytest.raises(K.DLayerError, match="multiple of n_kv_heads"):
+        K.attention_forward(x, x, x, 1, 128, 3, 2, 32, y, torch.zeros(512, device="cuda"))
+    with pytest.raises(K.DLayerError, match="multiple of 128"):
+        K.attention_forward(x, x, x, 1, 64, 2, 2, 32, y, torch.zeros(512, device="cuda"))
+    torch.cuda.synchronize()
+    assert (y == 3.0).all()
+    bad = si.CONFIGS["tiny"].with_(head_dim=48)
+    assert K.dlayer_saved_bytes(bad) == 0 and K.dlayer_workspace_bytes(bad) == 0
