@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Throughput of one decoder-layer training step (forward + backward) on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 8b|1b|small|tiny]
+
+A step is dlayer_forward + dlayer_backward over one batch of seeded synthetic bf16 inputs that are
+resident in HBM before the timed region starts.  Prints ONE JSON line: whole-step TFLOP/s
+(algorithmic FLOPs: 3 x forward, causal attention counted as half of the dense S^2 products, no
+credit for recomputation), tokens/s, the roofline figure of the dominant kernel (the bf16 MFMA GEMM,
+timed per launch with events on the launch stream) and the fp64 oracle timed on the host cores on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/s)
+
+
+def _describe(cfg):
+    return (f"decoder layer B{cfg.batch} S{cfg.seq} D{cfg.d_model} {cfg.n_q_heads}q/{cfg.n_kv_heads}kv x"
+            f"{cfg.head_dim} F{cfg.d_ff} rope_base {cfg.rope_base:g}, fwd+bwd")
+
+
+def cpu_baseline(cfg, budget_tokens):
+    """The fp64 oracle, as it stands, on a bounded sample: the same layer (same weights and widths)
+    on one batch row cut to `budget_tokens` positions."""
+    import numpy as np
+    from oracle import decoder_layer as odl
+    from synth import inputs as si
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    sub = cfg.with_(batch=1, seq=min(cfg.seq, budget_tokens))
+    inp = si.to_f64(si.make_layer_inputs(sub, seed=0))
+    x, dy = inp.pop("x"), inp.pop("dy")
+    t0 = time.perf_counter()
+    f = odl.layer_forward(sub, x, inp)
+    odl.layer_backward(sub, x, inp, dy, f)
+    dt = time.perf_counter() - t0
+    flops = si.layer_fwd_bwd_flops(sub)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "seconds": dt, "tokens_per_s": sub.tokens / dt,
+            "sample": f"same layer and weights, 1 batch row cut to {sub.seq} positions "
+                      f"({sub.tokens} of {cfg.tokens} tokens), fp64 NumPy, fwd+bwd"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=4096)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU decoder-layer step; this build has no multi-GPU path "
+              "(no collectives, no sharding): run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2602_08387_amd as K   # raises if the HIP library is not built: no fallback
+    from synth import inputs as si
+    from tests.parity import dev_bf16
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = si.CONFIGS[args.config]
+    inp = si.make_layer_inputs(cfg, seed=0)
+    x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])
+    w = {n: dev_bf16(inp[n]) for n in si.WEIGHT_NAMES}
+    del inp
+    dw = {n: torch.empty_like(t) for n, t in w.items()}
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    saved = torch.empty(K.dlayer_saved_bytes(cfg), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(K.dlayer_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+
+    def step():
+        K.dlayer_forward(cfg, x, w, y, saved, ws)
+        K.dlayer_backward(cfg, x, w, dy, saved, dx, dw, 0, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms = e0.elapsed_time(e1) / args.steps
+    ms = max(ms, wall_ms) if abs(ms - wall_ms) > 0.2 * wall_ms else ms
+    flops = si.layer_fwd_bwd_flops(cfg)
+    tflops = flops / (ms * 1e-3) / 1e12
+
+    # Forward and backward separately (informational).
+    def timed(fn, n):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+    n_sub = max(3, args.steps // 2)
+    fwd_ms = timed(lambda: K.dlayer_forward(cfg, x, w, y, saved, ws), n_sub)
+    bwd_ms = timed(lambda: K.dlayer_backward(cfg, x, w, dy, saved, dx, dw, 0, ws), n_sub)
+
+    # Dominant kernel: the k-major x k-major bf16 MFMA GEMM (all seven forward projections of the
+    # step run on it).  Replay exactly those seven launches, one event pair per launch on the launch
+    # stream, and compare algorithmic FLOPs with the summed durations.
+    T, D, F = cfg.tokens, cfg.d_model, cfg.d_ff
+    QD, KD = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    acts = {D: x.view(T, D), QD: torch.empty(T, QD, dtype=torch.bfloat16, device="cuda").normal_(),
+            F: torch.empty(T, F, dtype=torch.bfloat16, device="cuda").normal_()}
+    launches = [("wq", D, QD), ("wk", D, KD), ("wv", D, KD), ("wo", QD, D), ("w_gate", D, F), ("w_up", D, F),
+                ("w_down", F, D)]
+    outs = {n: torch.empty(T, N, dtype=torch.bfloat16, device="cuda") for n, _, N in launches}
+    reps = max(3, min(10, args.steps))
+    dur_ms, gemm_flops = [], 0.0
+    for r in range(reps + 1):
+        for n, Kd, N in launches:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            K.linear_forward(acts[Kd], w[n], None, T, Kd, N, outs[n])
+            b.record()
+            if r > 0:
+                dur_ms.append((a, b))
+                gemm_flops += 2.0 * T * Kd * N
+    torch.cuda.synchronize()
+    total_ms = sum(a.elapsed_time(b) for a, b in dur_ms)
+    achieved = gemm_flops / (total_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel<256,256,2,4,k-major,k-major> (7 projection launches/step)",
+                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                "avg_launch_ms": total_ms / len(dur_ms), "launches_timed": len(dur_ms), "traffic": None}
+
+    out = {
+        "metric": "decoder-layer fwd+bwd TFLOP/s", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": _describe(cfg), "name": args.config, "tokens_per_step": cfg.tokens,
+                   "flops_per_step": flops},
+        "tokens_per_s": cfg.tokens / (ms * 1e-3), "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "peak_tflops": PEAK_BF16_TFLOPS, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "paper_throughput": "not reported in the paper's text (Fig. 2b is an image; 8B Llama-3, Leonardo)",
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

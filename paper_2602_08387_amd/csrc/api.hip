@@ -64,7 +64,9 @@ static const char* cfg_problem(const dlayer_cfg* c) {
   if (c->n_q_heads % c->n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
   if (c->seq % 128) return "seq must be a multiple of 128";
   if (c->d_model % 64 || c->d_ff % 64) return "d_model and d_ff must be multiples of 64";
-  if (c->d_model > 4096 * 4) return "d_model above 16384 is not supported";
+  if ((c->n_q_heads * c->head_dim) % 64 || (c->n_kv_heads * c->head_dim) % 64)
+    return "n_q_heads*head_dim and n_kv_heads*head_dim must be multiples of 64";
+  if (c->d_model > 4096) return "d_model above 4096 is not supported";
   if (c->rope_layout != 0 && c->rope_layout != 1) return "rope_layout must be 0 or 1";
   if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return "rms_eps must be >= 0 and rope_base > 0";
   const int64_t T = (int64_t)c->batch * c->seq;

@@ -173,9 +173,19 @@ int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, cons
   const size_t lds = (size_t)kRmsBwdWaves * D * sizeof(float);
   dim3 grid(nb), block(64 * kRmsBwdWaves);
 #define RMS_BWD(NV)                                                                             \
-  hipLaunchKernelGGL(rmsnorm_bwd_kernel<NV>, grid, block, lds, st, (const bf16_t*)x,            \
-                     (const bf16_t*)gamma, rstd, (const bf16_t*)dh, (const bf16_t*)dres,        \
-                     (bf16_t*)dx, (float*)workspace, T, (int)D)
+  do {                                                                                          \
+    static bool attr_set = false;                                                               \
+    if (!attr_set) {                                                                            \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(rmsnorm_bwd_kernel<NV>), \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,            \
+                                         kRmsBwdWaves * NV * 512 * (int)sizeof(float));         \
+      if (e != hipSuccess) return fail(-3, "rmsnorm_backward: LDS reservation failed: %s", hipGetErrorString(e)); \
+      attr_set = true;                                                                          \
+    }                                                                                           \
+    hipLaunchKernelGGL(rmsnorm_bwd_kernel<NV>, grid, block, lds, st, (const bf16_t*)x,          \
+                       (const bf16_t*)gamma, rstd, (const bf16_t*)dh, (const bf16_t*)dres,      \
+                       (bf16_t*)dx, (float*)workspace, T, (int)D);                              \
+  } while (0)
   if (nv <= 1) RMS_BWD(1);
   else if (nv <= 2) RMS_BWD(2);
   else if (nv <= 4) RMS_BWD(4);
