@@ -34,7 +34,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t attn_rsrc(const void* p, uint3
 }
 
 // [ROWS][DH] bf16 tile in LDS, DH*2 bytes per row, 16-byte chunk c of row r stored at chunk
-// c ^ (r & SWZ_MASK).  Loaded by NW waves with 1 KiB wave-wide async loads.
+// c ^ swz(r).  Loaded by NW waves with 1 KiB wave-wide async loads.  swz is chosen so that both
+// access patterns are free of bank conflicts (the LDS serves 256 B of banks per clock):
+//   row reads  (ds_read_b128, 16 lanes = 16 consecutive rows, one logical chunk), and
+//   transposed reads (ds_read_b64_tr_b16, 32 lanes = 4 consecutive rows x 64 B).
 template <int ROWS, int DH, int NW>
 struct RowTile {
   static constexpr int ROW_B = DH * 2;
@@ -42,8 +45,12 @@ struct RowTile {
   static constexpr int RPI = 1024 / ROW_B;    // rows per wave-wide load
   static constexpr int NINSTR = ROWS / RPI;
   static constexpr int PER_WAVE = NINSTR / NW;
-  static constexpr int SWZ_MASK = (LPR - 1) < 7 ? (LPR - 1) : 7;
-  static_assert(NINSTR % NW == 0 && ((ROWS / NW) % 8) == 0, "tile split");
+  static __device__ __forceinline__ int swz(int row) {
+    if constexpr (LPR == 16) { const int i = row & 15; return ((i & 3) << 2) | (i >> 2); }
+    else if constexpr (LPR == 8) { const int i = (row >> 1) & 7; return ((i & 1) << 2) | (i >> 1); }
+    else { return (row >> 2) & 3; }
+  }
+  static_assert(NINSTR % NW == 0 && ((ROWS / NW) % 16) == 0, "tile split");
   static constexpr int BYTES = ROWS * ROW_B;
 
   // rs describes memory starting at the tile's first row; ld = row stride in elements.
@@ -53,7 +60,7 @@ struct RowTile {
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
       const int j = wave * PER_WAVE + i;
-      const int c = pc ^ ((i * RPI + r) & SWZ_MASK);
+      const int c = pc ^ swz(i * RPI + r);   // rows per wave are a multiple of 16
       const uint32_t vo = (uint32_t)(r * ld * 2 + (c << 4));
       const uint32_t so = (uint32_t)((int64_t)j * RPI * ld * 2);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, vo, so, 0, 0);
@@ -62,7 +69,7 @@ struct RowTile {
   // MFMA operand for rows row0 + lane%32, contraction over the DH index, step kk (16 of DH).
   static __device__ __forceinline__ bf16x8 frag_rows(const char* t, int row0, int kk, int lane) {
     const int row = row0 + (lane & 31);
-    const int c = (kk * 2 + (lane >> 5)) ^ (row & SWZ_MASK);
+    const int c = (kk * 2 + (lane >> 5)) ^ swz(row);
     return *reinterpret_cast<const bf16x8*>(t + row * ROW_B + (c << 4));
   }
   // MFMA operand for "rows" = 32 columns of the tile starting at col0 (the DH index), contraction
@@ -71,9 +78,9 @@ struct RowTile {
     const int grp = lane >> 4, s = lane & 15, e = s >> 2, g = s & 3;
     const int col = col0 + ((grp & 1) << 4) + (g << 2);
     const int row = krow0 + ((grp >> 1) << 2) + e;
-    const char* p0 = t + row * ROW_B + ((((col >> 3) ^ (row & SWZ_MASK)) << 4) | ((col & 7) << 1));
+    const char* p0 = t + row * ROW_B + ((((col >> 3) ^ swz(row)) << 4) | ((col & 7) << 1));
     const int row2 = row + 8;
-    const char* p1 = t + row2 * ROW_B + ((((col >> 3) ^ (row2 & SWZ_MASK)) << 4) | ((col & 7) << 1));
+    const char* p1 = t + row2 * ROW_B + ((((col >> 3) ^ swz(row2)) << 4) | ((col & 7) << 1));
     bf16x8 v;
     v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p0));
     v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p1));

@@ -3,25 +3,35 @@
 // layer (y = x W^T, dx = dy W, dW = dy^T x): each operand may be stored with the contraction
 // index contiguous ("k-major") or with its M/N index contiguous ("mn-major").
 //
-// Data path: global --buffer_load ... lds (16 B per lane, no VGPR staging)--> LDS (two stages
-// of BK = 64) --ds_read_b128 (k-major) or ds_read_b64_tr_b16 (mn-major)--> MFMA operands.
-// The buffer descriptor's range check zero-fills rows past the end of a matrix, so M and N
-// need not be tile multiples; K_s must be a multiple of 64.
+// Data path: global --buffer_load ... lds (16 B per lane, no VGPR staging)--> LDS ring of NS
+// stages, BK k-values each --ds_read_b128 (k-major) or ds_read_b64_tr_b16 (mn-major)--> MFMA
+// operands.  Loads run NS-1 K-steps ahead of the MFMAs.  The buffer descriptor's range check
+// zero-fills rows past the end of a matrix, so M and N need not be tile multiples; K_s must be a
+// multiple of 64.
 //
 // LDS layouts (the async load puts lane l's 16 bytes at chunk l of a 1 KiB span, so swizzles
-// are applied on the global-address side):
-//   k-major tile  [rows][64 k]   : 128 B per row = 8 chunks; chunk c of row r sits at c ^ (r & 7).
-//   mn-major tile [64 k][R mn]   : R/8 chunks per k-row; chunk c of k-row k sits at
-//                                  c ^ (((k & 3) << 2) & (R/8 - 1)).
+// are applied on the global-address side).  The LDS serves 256 B of banks per clock: a 16-byte
+// read is done 16 lanes at a time, an 8-byte transposed read 32 lanes at a time.
+//   k-major tile  [rows][BK k]   : BK*2 bytes per row = CPR chunks; chunk c of row r sits at
+//                                  c ^ ((r / (16/CPR)) & (CPR-1)), so 16 consecutive rows reading
+//                                  one logical chunk touch 16 different 16-byte bank groups.
+//   mn-major tile [BK k][R mn]   : R/8 chunks per k-row; chunk c of k-row k sits at
+//                                  c ^ (((k & 3) << 2) & (R/8 - 1)): the 4 k-rows x 64 B of a
+//                                  transposed read fall in 4 different 64-byte groups.
 // MFMA roles: the N-side operand feeds MFMA "A" (row index i), the M-side operand feeds MFMA
-// "B" (column index j), so a lane ends up with 4 consecutive n for one m and the epilogue
-// stores 8 bytes per lane into row-major C.
+// "B" (column index j), so a lane ends up with 4 consecutive n for one m.  The epilogue passes
+// the tile through LDS so that global stores (and residual loads) are 16 bytes per lane along
+// rows of C.
 #include "common.h"
 #include "kernels.h"
 
 namespace dl {
 
-constexpr int BK = 64;
+// Measured on MI355X (M=16384, K=4096, N=14336): 2 stages of 64 k-values 1223 TFLOP/s; 3, 4 and 5
+// stages of 32 k-values 1137, 1150 and 1136 TFLOP/s.  The step is not latency-bound: a deeper ring
+// only adds barriers.
+constexpr int BK = 64;   // k-values per pipeline stage
+constexpr int NS = 2;    // ring stages
 
 struct GemmKArgs {
   const bf16_t* a[3];
@@ -46,73 +56,111 @@ template <int R, bool KMAJOR, int NW>
 struct TileLoader {
   static constexpr int NINSTR = R * BK * 2 / 1024;  // wave-wide 1 KiB loads per tile
   static constexpr int PER_WAVE = NINSTR / NW;
-  static_assert(NINSTR % NW == 0, "tile loads must divide across waves");
+  static_assert(NINSTR % NW == 0 && PER_WAVE >= 1, "tile loads must divide across waves");
+  static constexpr int CPRK = BK / 8;               // chunks per row of a k-major tile
+  static constexpr int RPW = 16 / CPRK;             // k-major rows per 256-byte bank window
   static constexpr int CPR = R / 8;                 // chunks per k-row (mn-major)
-  static constexpr int RPI = KMAJOR ? 8 : 1024 / (R * 2);  // tile rows per instruction
-
-  uint32_t voff[KMAJOR ? 1 : (RPI >= 4 ? 1 : 4 / RPI)];
+  static constexpr int RPI = KMAJOR ? 1024 / (BK * 2) : 1024 / (R * 2);  // tile rows per instruction
+  // swizzle variants a lane needs across its instructions
+  static constexpr int NVAR = KMAJOR ? (RPI >= 16 ? 1 : 16 / RPI) : (RPI >= 4 ? 1 : 4 / RPI);
+  static_assert(PER_WAVE % NVAR == 0, "swizzle variant must not depend on the wave index");
+  uint32_t voff[NVAR];
 
   __device__ __forceinline__ void init(int lane, int64_t ld) {
     if constexpr (KMAJOR) {
-      voff[0] = (uint32_t)((lane >> 3) * ld * 2 + (((lane & 7) ^ (lane >> 3)) << 4));
-    } else {
-      constexpr int NVAR = RPI >= 4 ? 1 : 4 / RPI;
+      // instruction j covers rows RPI*j ..; the swizzle depends on (row / RPW) & (CPRK - 1)
 #pragma unroll
       for (int v = 0; v < NVAR; ++v) {
-        const int krow = v * RPI + lane / CPR;  // k-row within a group of 4 (only k & 3 matters)
-        const int pc = lane % CPR;
-        const int c = pc ^ (((krow & 3) << 2) & (CPR - 1));
+        const int row = v * RPI + lane / CPRK;   // row modulo 16
+        const int c = (lane % CPRK) ^ ((row / RPW) & (CPRK - 1));
+        voff[v] = (uint32_t)((lane / CPRK) * ld * 2 + (c << 4));
+      }
+    } else {
+#pragma unroll
+      for (int v = 0; v < NVAR; ++v) {
+        const int krow = v * RPI + lane / CPR;  // k-row modulo 4
+        const int c = (lane % CPR) ^ (((krow & 3) << 2) & (CPR - 1));
         voff[v] = (uint32_t)((lane / CPR) * ld * 2 + (c << 4));
       }
     }
   }
 
-  // lds_tile: byte offset of this tile's stage in LDS (uniform).  k0: k origin (uniform).
-  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, char* smem, int lds_tile, int wave,
-                                        int64_t ld, int k0) const {
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, char* lds_tile, int wave, int64_t ld,
+                                        int k0) const {
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
       const int j = wave * PER_WAVE + i;
-      uint32_t soff, vo;
-      if constexpr (KMAJOR) {
-        soff = (uint32_t)(((int64_t)8 * j * ld + k0) * 2);
-        vo = voff[0];
-      } else {
-        constexpr int NVAR = RPI >= 4 ? 1 : 4 / RPI;
-        static_assert(PER_WAVE % NVAR == 0, "swizzle variant must not depend on the wave index");
-        soff = (uint32_t)(((int64_t)(k0 + j * RPI) * ld) * 2);
-        vo = voff[i % NVAR];
-      }
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(smem + lds_tile + j * 1024), 16, vo,
+      const uint32_t soff = KMAJOR ? (uint32_t)(((int64_t)RPI * j * ld + k0) * 2)
+                                   : (uint32_t)(((int64_t)(k0 + j * RPI) * ld) * 2);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, voff[i % NVAR],
                                                soff, 0, 0);
     }
   }
 };
 
-// Reads the MFMA operand fragment for 32 rows starting at row0 (tile-local M/N index), k-substep
-// kk (16 k), from a tile stored in LDS at `tile`.
+// MFMA operand fragment for 32 rows starting at row0 (tile-local M/N index), k-substep kk (16 k).
 template <int R, bool KMAJOR>
 __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row0, int kk, int lane) {
   if constexpr (KMAJOR) {
+    constexpr int CPRK = BK / 8, RPW = 16 / CPRK;
     const int row = row0 + (lane & 31);
-    const int c = (kk * 2 + (lane >> 5)) ^ (row & 7);
-    return *reinterpret_cast<const bf16x8*>(tile + row * 128 + (c << 4));
+    const int c = (kk * 2 + (lane >> 5)) ^ ((row / RPW) & (CPRK - 1));
+    return *reinterpret_cast<const bf16x8*>(tile + row * (BK * 2) + (c << 4));
   } else {
     constexpr int CPR = R / 8;
     const int grp = lane >> 4, s = lane & 15, e = s >> 2, g = s & 3;
     const int col = row0 + ((grp & 1) << 4) + (g << 2);
     const int krow = kk * 16 + ((grp >> 1) << 3) + e;
     const int f = ((krow & 3) << 2) & (CPR - 1);  // same for krow and krow + 4
-    const int byte = (((col >> 3) ^ f) << 4) + ((col & 7) << 1);
-    const char* p0 = tile + krow * (R * 2) + byte;
-    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p0));
-    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p0 + 4 * R * 2));
+    const char* p0 = tile + krow * (R * 2) + ((((col >> 3) ^ f) << 4) | ((col & 7) << 1));
     bf16x8 v;
-    v.lo = lo;
-    v.hi = hi;
+    v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p0));
+    v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p0 + 4 * R * 2));
     return v;
   }
 }
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Position of the next tile pair to fetch: segment, k offset, and that segment's descriptors.
+template <int BM, int BN, int NW, bool AK, bool BKM>
+struct LoadCursor {
+  TileLoader<BM, AK, NW> la;
+  TileLoader<BN, BKM, NW> lb;
+  __amdgpu_buffer_rsrc_t ra, rb;
+  int64_t lda, ldb;
+  int seg = 0, k = 0;
+
+  __device__ __forceinline__ void open(const GemmKArgs& p, int s, int m0, int n0, int lane) {
+    const int K = p.K[s];
+    lda = p.lda[s];
+    ldb = p.ldb[s];
+    const bf16_t* ab = AK ? p.a[s] + (int64_t)m0 * lda : p.a[s] + m0;
+    const bf16_t* bb = BKM ? p.b[s] + (int64_t)n0 * ldb : p.b[s] + n0;
+    const uint32_t a_bytes = AK ? (uint32_t)((((int64_t)(p.M - m0 - 1)) * lda + K) * 2)
+                                : (uint32_t)((((int64_t)(K - 1)) * lda + (p.M - m0)) * 2);
+    const uint32_t b_bytes = BKM ? (uint32_t)((((int64_t)(p.N - n0 - 1)) * ldb + K) * 2)
+                                 : (uint32_t)((((int64_t)(K - 1)) * ldb + (p.N - n0)) * 2);
+    ra = make_rsrc(ab, a_bytes);
+    rb = make_rsrc(bb, b_bytes);
+    la.init(lane, lda);
+    lb.init(lane, ldb);
+  }
+  __device__ __forceinline__ void issue_next(const GemmKArgs& p, char* stage, int wave, int m0, int n0, int lane) {
+    if (seg < p.nseg) {
+      la.issue(ra, stage, wave, lda, k);
+      lb.issue(rb, stage + BM * BK * 2, wave, ldb, k);
+      k += BK;
+      if (k == p.K[seg]) {
+        k = 0;
+        if (++seg < p.nseg) open(p, seg, m0, n0, lane);
+      }
+    }
+  }
+};
 
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
@@ -120,6 +168,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int FM = TM / 32, FN = TN / 32;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  using LoadA = TileLoader<BM, AK, NW>;
+  using LoadB = TileLoader<BN, BKM, NW>;
+  constexpr int LPW = LoadA::PER_WAVE + LoadB::PER_WAVE;   // loads per wave per stage
+  static_assert((NS - 2) * LPW <= 63, "vmcnt range");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const int lane = threadIdx.x & 63;
@@ -142,9 +194,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   const int tile_n = in_band / band_h;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  TileLoader<BM, AK, NW> la;
-  TileLoader<BN, BKM, NW> lb;
-
   f32x16 acc[FN][FM];
 #pragma unroll
   for (int i = 0; i < FN; ++i)
@@ -153,101 +202,93 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  int stage = 0;
-  bool first = true;
-  for (int s = 0; s < p.nseg; ++s) {
-    const int K = p.K[s];
-    const int64_t lda = p.lda[s], ldb = p.ldb[s];
-    const bf16_t* ab = AK ? p.a[s] + (int64_t)m0 * lda : p.a[s] + m0;
-    const bf16_t* bb = BKM ? p.b[s] + (int64_t)n0 * ldb : p.b[s] + n0;
-    const uint32_t a_bytes =
-        AK ? (uint32_t)((((int64_t)(p.M - m0 - 1)) * lda + K) * 2) : (uint32_t)((((int64_t)(K - 1)) * lda + (p.M - m0)) * 2);
-    const uint32_t b_bytes =
-        BKM ? (uint32_t)((((int64_t)(p.N - n0 - 1)) * ldb + K) * 2) : (uint32_t)((((int64_t)(K - 1)) * ldb + (p.N - n0)) * 2);
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(ab, a_bytes), rb = make_rsrc(bb, b_bytes);
-    la.init(lane, lda);
-    lb.init(lane, ldb);
-    const int KT = K / BK;
-    if (first) {
-      la.issue(ra, smem, 0, wave, lda, 0);
-      lb.issue(rb, smem, A_BYTES, wave, ldb, 0);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      first = false;
+  int total = 0;
+  for (int s = 0; s < p.nseg; ++s) total += p.K[s] / BK;
+
+  // Load cursor: runs NS-1 K-steps ahead of the compute cursor, across segment boundaries.
+  LoadCursor<BM, BN, NW, AK, BKM> cur;
+  cur.open(p, 0, m0, n0, lane);
+#pragma unroll
+  for (int i = 0; i < NS - 1; ++i) cur.issue_next(p, smem + i * STAGE, wave, m0, n0, lane);
+  if (total >= NS - 1) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  for (int t = 0; t < total; ++t) {
+    cur.issue_next(p, smem + ((t + NS - 1) % NS) * STAGE, wave, m0, n0, lane);
+    const char* ta = smem + (t % NS) * STAGE;
+    const char* tb = ta + A_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 fa[FM], fb[FN];
+#pragma unroll
+      for (int j = 0; j < FM; ++j) fa[j] = read_frag<BM, AK>(ta, wave_m * TM + j * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < FN; ++i) fb[i] = read_frag<BN, BKM>(tb, wave_n * TN + i * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
     }
-    for (int kt = 0; kt < KT; ++kt) {
-      const char* ta = smem + stage * STAGE;
-      const char* tb = ta + A_BYTES;
-      if (kt + 1 < KT) {
-        la.issue(ra, smem, (stage ^ 1) * STAGE, wave, lda, (kt + 1) * BK);
-        lb.issue(rb, smem, (stage ^ 1) * STAGE + A_BYTES, wave, ldb, (kt + 1) * BK);
-      } else if (s + 1 < p.nseg) {
-        // first K-step of the next segment
-        const int64_t lda2 = p.lda[s + 1], ldb2 = p.ldb[s + 1];
-        const int K2 = p.K[s + 1];
-        const bf16_t* ab2 = AK ? p.a[s + 1] + (int64_t)m0 * lda2 : p.a[s + 1] + m0;
-        const bf16_t* bb2 = BKM ? p.b[s + 1] + (int64_t)n0 * ldb2 : p.b[s + 1] + n0;
-        const uint32_t a2 = AK ? (uint32_t)((((int64_t)(p.M - m0 - 1)) * lda2 + K2) * 2)
-                               : (uint32_t)((((int64_t)(K2 - 1)) * lda2 + (p.M - m0)) * 2);
-        const uint32_t b2 = BKM ? (uint32_t)((((int64_t)(p.N - n0 - 1)) * ldb2 + K2) * 2)
-                                : (uint32_t)((((int64_t)(K2 - 1)) * ldb2 + (p.N - n0)) * 2);
-        TileLoader<BM, AK, NW> la2;
-        TileLoader<BN, BKM, NW> lb2;
-        la2.init(lane, lda2);
-        lb2.init(lane, ldb2);
-        la2.issue(make_rsrc(ab2, a2), smem, (stage ^ 1) * STAGE, wave, lda2, 0);
-        lb2.issue(make_rsrc(bb2, b2), smem, (stage ^ 1) * STAGE + A_BYTES, wave, ldb2, 0);
-      }
-#pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8 fa[FM], fb[FN];
-#pragma unroll
-        for (int j = 0; j < FM; ++j) fa[j] = read_frag<BM, AK>(ta, wave_m * TM + j * 32, kk, lane);
-#pragma unroll
-        for (int i = 0; i < FN; ++i) fb[i] = read_frag<BN, BKM>(tb, wave_n * TN + i * 32, kk, lane);
-#pragma unroll
-        for (int i = 0; i < FN; ++i)
-#pragma unroll
-          for (int j = 0; j < FM; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
-      }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      stage ^= 1;
-    }
+    // stage t+1 must have landed; the NS-2 younger groups may still be in flight
+    if (t + NS - 1 < total) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
   }
 
-  // Epilogue: lane holds, per 32x32 MFMA tile, column m = lane % 32 and rows
-  // n = 8*(r/4) + 4*(lane/32) + r%4 of acc (acc is indexed [n][m]).
+  // Epilogue through LDS: each wave owns a [TM][64] bf16 staging area per 64 columns of its tile
+  // (128 bytes per row, chunk c of row m stored at c ^ ((m >> 1) & 7)), filled from the accumulator
+  // layout (8 bytes per lane) and drained row-contiguously (16 bytes per lane, 8 lanes per row).
+  static_assert(TN % 64 == 0, "staging layout assumes 128-byte rows");
+  char* stg = smem + wave * (TM * 128);
   const int lm = lane & 31, lh = lane >> 5;
+  const int rrow = lane >> 3, rpc = lane & 7;
 #pragma unroll
-  for (int j = 0; j < FM; ++j) {
-    const int m = m0 + wave_m * TM + j * 32 + lm;
-    if (m < p.M) {
-      bf16_t* crow = p.c + (int64_t)m * p.ldc;
-      const bf16_t* rrow = p.r ? p.r + (int64_t)m * p.ldc : nullptr;
+  for (int nb = 0; nb < TN / 64; ++nb) {
+    const int nbase = n0 + wave_n * TN + nb * 64;
+    if (p.r || p.accumulate) {
+      const bf16_t* src = p.r ? p.r : p.c;
 #pragma unroll
-      for (int i = 0; i < FN; ++i) {
+      for (int t = 0; t < TM / 8; ++t) {
+        const int row = t * 8 + rrow;
+        const int m = m0 + wave_m * TM + row;
+        const int n = nbase + ((rpc ^ ((row >> 1) & 7)) << 3);
+        bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (m < p.M && n < p.N) v = *reinterpret_cast<const bf16x8*>(src + (int64_t)m * p.ldc + n);
+        *reinterpret_cast<bf16x8*>(stg + row * 128 + (rpc << 4)) = v;
+      }
+#pragma unroll
+      for (int j = 0; j < FM; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int row = j * 32 + lm, c = i * 4 + g;
+            const bf16x4 v = *reinterpret_cast<const bf16x4*>(stg + row * 128 + ((c ^ ((row >> 1) & 7)) << 4) + lh * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[nb * 2 + i][j][g * 4 + e] += (float)v[e];
+          }
+    }
+#pragma unroll
+    for (int j = 0; j < FM; ++j)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int n = n0 + wave_n * TN + i * 32 + g * 8 + lh * 4;
-          if (n < p.N) {
-            float v0 = acc[i][j][g * 4 + 0], v1 = acc[i][j][g * 4 + 1], v2 = acc[i][j][g * 4 + 2],
-                  v3 = acc[i][j][g * 4 + 3];
-            if (rrow) {
-              bf16x4 rv = *reinterpret_cast<const bf16x4*>(rrow + n);
-              v0 += (float)rv[0]; v1 += (float)rv[1]; v2 += (float)rv[2]; v3 += (float)rv[3];
-            }
-            if (p.accumulate) {
-              bf16x4 cv = *reinterpret_cast<const bf16x4*>(crow + n);
-              v0 += (float)cv[0]; v1 += (float)cv[1]; v2 += (float)cv[2]; v3 += (float)cv[3];
-            }
-            bf16x4 o;
-            o[0] = (bf16_t)v0; o[1] = (bf16_t)v1; o[2] = (bf16_t)v2; o[3] = (bf16_t)v3;
-            *reinterpret_cast<bf16x4*>(crow + n) = o;
-          }
+          const int row = j * 32 + lm, c = i * 4 + g;
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[nb * 2 + i][j][g * 4 + e];
+          *reinterpret_cast<bf16x4*>(stg + row * 128 + ((c ^ ((row >> 1) & 7)) << 4) + lh * 8) = o;
         }
-      }
+#pragma unroll
+    for (int t = 0; t < TM / 8; ++t) {
+      const int row = t * 8 + rrow;
+      const int m = m0 + wave_m * TM + row;
+      const int n = nbase + ((rpc ^ ((row >> 1) & 7)) << 3);
+      const bf16x8 v = *reinterpret_cast<const bf16x8*>(stg + row * 128 + (rpc << 4));
+      if (m < p.M && n < p.N) *reinterpret_cast<bf16x8*>(p.c + (int64_t)m * p.ldc + n) = v;
     }
   }
 }
@@ -258,7 +299,8 @@ static int launch_cfg(const GemmKArgs& k, bool ak, bool bk, hipStream_t st) {
   a.tiles_m = (k.M + BM - 1) / BM;
   a.tiles_n = (k.N + BN - 1) / BN;
   const dim3 grid((unsigned)(a.tiles_m * a.tiles_n)), block(WM * WN * 64);
-  const size_t lds = 2 * (size_t)(BM + BN) * BK * 2;
+  const size_t ring = (size_t)NS * (BM + BN) * BK * 2, staging = (size_t)WM * WN * (BM / WM) * 128;
+  const size_t lds = ring > staging ? ring : staging;
 #define GEMM_LAUNCH(AK_, BK_)                                                                    \
   do {                                                                                           \
     auto kern = gemm_kernel<BM, BN, WM, WN, AK_, BK_>;                                           \
