@@ -1,0 +1,106 @@
+"""GPU parity of the whole training step around the layers: embedding -> L decoder layers -> final
+RMSNorm -> LM head -> mean softmax cross-entropy, and back to the embedding gradients, composed from
+the C-ABI entry points and compared with the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lm_stack as olm
+from synth import inputs as si
+from tests.parity import assert_close, dev_bf16, host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def K():
+    import paper_2602_08387_amd as k
+    return k
+
+
+def _buf(n):
+    return torch.full((max(int(n), 256),), 0xFF, dtype=torch.uint8, device="cuda")
+
+
+def run_stack(K, cfg, raw, V):
+    """Pointer plumbing only: every arithmetic step is a library call."""
+    B, S, D = cfg.batch, cfg.seq, cfg.d_model
+    T, L = B * S, len(raw["layers"])
+    ids = torch.from_numpy(raw["ids"].reshape(-1)).cuda()
+    tgt = torch.from_numpy(raw["targets"].reshape(-1)).cuda()
+    E, w_lm, g_f = dev_bf16(raw["embed"]), dev_bf16(raw["w_lm"]), dev_bf16(raw["g_final"])
+    W = [{n: dev_bf16(w[n]) for n in si.WEIGHT_NAMES} for w in raw["layers"]]
+    bf = lambda *s: torch.full(s, float("nan"), dtype=torch.bfloat16, device="cuda")
+    xs = [bf(T, D) for _ in range(L + 1)]
+    saved = [_buf(K.dlayer_saved_bytes(cfg)) for _ in range(L)]
+    ws = _buf(K.dlayer_workspace_bytes(cfg))
+    K.embed_forward(E, ids, T, V, D, xs[0])
+    for l in range(L):
+        K.dlayer_forward(cfg, xs[l], W[l], xs[l + 1], saved[l], ws)
+    h_f, rstd_f = bf(T, D), torch.empty(T, dtype=torch.float32, device="cuda")
+    K.rmsnorm_forward(xs[L], g_f, T, D, cfg.rms_eps, h_f, rstd_f)
+    logits = bf(T, V)
+    K.linear_forward(h_f, w_lm, None, T, D, V, logits)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    K.ce_loss_fwd_bwd(logits, tgt, T, V, 1.0, loss, logits, _buf(K.ce_loss_workspace_bytes(T, V)))  # in place
+    dh_f, dw_lm = bf(T, D), bf(V, D)
+    K.linear_backward(h_f, w_lm, logits, T, D, V, dh_f, dw_lm, 0, None)
+    dx, dg_f = bf(T, D), bf(D)
+    K.rmsnorm_backward(xs[L], g_f, rstd_f, dh_f, None, T, D, dx, dg_f, 0, _buf(K.rmsnorm_backward_workspace_bytes(T, D)))
+    dW = [{n: torch.full_like(t, float("nan")) for n, t in W[l].items()} for l in range(L)]
+    for l in reversed(range(L)):
+        dx_prev = bf(T, D)
+        K.dlayer_backward(cfg, xs[l], W[l], dx, saved[l], dx_prev, dW[l], 0, ws)
+        dx = dx_prev
+    dE = bf(V, D)
+    K.embed_backward(dx, ids, T, V, D, dE)
+    torch.cuda.synchronize()
+    return {"loss": loss.item(), "dx0": dx, "embed": dE, "w_lm": dw_lm, "g_final": dg_f, "layers": dW, "y": xs[L]}
+
+
+def test_stack_matches_oracle(K):
+    cfg = si.LayerConfig(2, 256, 256, 4, 2, 64, 512, 1e-5, 500000.0, 0)
+    V, L = 4096, 3
+    raw = si.make_stack_inputs(cfg, L, V, seed=0)
+    raw["ids"][0, :40] = 17          # repeated ids exercise the scatter-add
+    s = si.to_f64(raw)
+    args = (cfg, s["ids"], s["targets"], s["embed"], s["layers"], s["g_final"], s["w_lm"])
+    st = olm.stack_forward(*args)
+    ref = olm.stack_backward(*args, st)
+    got = run_stack(K, cfg, raw, V)
+    assert abs(got["loss"] - st["loss"]) <= 2e-2 * abs(st["loss"]), (got["loss"], st["loss"])
+    assert abs(got["loss"] - st["loss"]) <= 2e-3 * abs(st["loss"])   # what the arithmetic actually gives
+    # the stack's bar is on the scalar loss; the hidden state after three layers carries three layers
+    # of bf16 rounding noise, so its element-wise bound is wider than one layer's
+    assert_close(got["y"], st["x"][-1].reshape(-1, cfg.d_model), "stack:x_L", rel_tol=5e-2)
+    for name in ("dx0", "embed", "w_lm", "g_final"):
+        assert_close(got[name], ref[name], "stack:" + name, rel_tol=np.inf)
+    for l in range(L):
+        for n in si.WEIGHT_NAMES:
+            assert_close(got["layers"][l][n], ref["layers"][l][n], f"stack:layer{l}.d{n}", rel_tol=np.inf)
+    print("loss", got["loss"], st["loss"])
+
+
+def test_lm_head_and_loss_at_full_vocab_width(K):
+    """LM head 4096 x 128256 with the fused loss, on 256 token rows (the oracle's share of the
+    8192-row workload): loss, dh_f and sampled rows of dW_lm."""
+    T, D, V = 256, 4096, si.VOCAB_8B
+    rng = np.random.Generator(np.random.PCG64(5))
+    hb = si._normal_bf16(rng, (T, D))
+    wb = si._normal_bf16(rng, (V, D), std=0.02)
+    tg = rng.integers(0, V, T)
+    h, w = si.bf16_bits_to_f64(hb), si.bf16_bits_to_f64(wb)
+    logits = h @ w.T
+    loss_ref, dlg, _ = olm.ce_loss_fwd_bwd(logits, tg)
+    hd, wd, td = dev_bf16(hb), dev_bf16(wb), torch.from_numpy(tg).cuda()
+    lg = torch.empty(T, V, dtype=torch.bfloat16, device="cuda")
+    K.linear_forward(hd, wd, None, T, D, V, lg)
+    assert_close(lg, logits, "logits", rel_tol=8e-3)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    K.ce_loss_fwd_bwd(lg, td, T, V, 1.0, loss, lg, _buf(K.ce_loss_workspace_bytes(T, V)))
+    assert abs(loss.item() - loss_ref) <= 1e-3 * loss_ref
+    dh, dw = torch.empty_like(hd), torch.empty_like(wd)
+    K.linear_backward(hd, wd, lg, T, D, V, dh, dw, 0, None)
+    assert_close(dh, dlg @ w, "dh_f", rel_tol=np.inf)
+    rows = np.concatenate([tg[:32], rng.integers(0, V, 96)])
+    assert_close(host_f64(dw)[rows], dlg[:, rows].T @ h, "dW_lm[sampled rows]", rel_tol=np.inf)
