@@ -1,5 +1,5 @@
 // bf16 GEMM for gfx950: C[M,N] = sum_s opA_s[M,K_s] * opB_s[K_s,N] (+R) with fp32 accumulation
-// on v_mfma_f32_32x32x16_bf16.  One kernel template serves the three products of a linear
+// on v_mfma_f32_16x16x32_bf16.  One kernel template serves the three products of a linear
 // layer (y = x W^T, dx = dy W, dW = dy^T x): each operand may be stored with the contraction
 // index contiguous ("k-major") or with its M/N index contiguous ("mn-major").
 //
@@ -27,11 +27,22 @@
 
 namespace dl {
 
-// Measured on MI355X (M=16384, K=4096, N=14336): 2 stages of 64 k-values 1223 TFLOP/s; 3, 4 and 5
-// stages of 32 k-values 1137, 1150 and 1136 TFLOP/s.  The step is not latency-bound: a deeper ring
-// only adds barriers.
+// Measured on MI355X (M=16384, K=4096, N=14336, normal data): 2 stages of 64 k-values beat 3, 4 and 5
+// stages of 32 (the K-step is not latency-bound, a deeper ring only adds barriers); 16x16x32 MFMA
+// blocks beat 32x32x16 by 3 % on y = x W^T and 11 % on dx = dy W (half the accumulator traffic per
+// flop); 8 waves of 128x64 beat 4 waves of 128x128 under the compiler's schedule.
 constexpr int BK = 64;   // k-values per pipeline stage
 constexpr int NS = 2;    // ring stages
+constexpr int MI = 16;               // MFMA block edge: 32 (32x32x16) or 16 (16x16x32)
+constexpr int KSTEP = MI == 32 ? 16 : 32;  // k per MFMA
+constexpr int NACC = MI * MI / 64;       // accumulator registers per MFMA block
+typedef float acc_t __attribute__((ext_vector_type(NACC)));
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
 
 struct GemmKArgs {
   const bf16_t* a[3];
@@ -98,19 +109,19 @@ struct TileLoader {
   }
 };
 
-// MFMA operand fragment for 32 rows starting at row0 (tile-local M/N index), k-substep kk (16 k).
+// MFMA operand fragment for MI rows starting at row0 (tile-local M/N index), k-substep kk (KSTEP k).
 template <int R, bool KMAJOR>
 __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row0, int kk, int lane) {
   if constexpr (KMAJOR) {
     constexpr int CPRK = BK / 8, RPW = 16 / CPRK;
-    const int row = row0 + (lane & 31);
-    const int c = (kk * 2 + (lane >> 5)) ^ ((row / RPW) & (CPRK - 1));
+    const int row = row0 + (lane & (MI - 1));
+    const int c = (kk * (KSTEP / 8) + lane / MI) ^ ((row / RPW) & (CPRK - 1));
     return *reinterpret_cast<const bf16x8*>(tile + row * (BK * 2) + (c << 4));
   } else {
     constexpr int CPR = R / 8;
     const int grp = lane >> 4, s = lane & 15, e = s >> 2, g = s & 3;
-    const int col = row0 + ((grp & 1) << 4) + (g << 2);
-    const int krow = kk * 16 + ((grp >> 1) << 3) + e;
+    const int col = MI == 32 ? row0 + ((grp & 1) << 4) + (g << 2) : row0 + (g << 2);
+    const int krow = MI == 32 ? kk * 16 + ((grp >> 1) << 3) + e : kk * 32 + (grp << 3) + e;
     const int f = ((krow & 3) << 2) & (CPR - 1);  // same for krow and krow + 4
     const char* p0 = tile + krow * (R * 2) + ((((col >> 3) ^ f) << 4) | ((col & 7) << 1));
     bf16x8 v;
@@ -166,7 +177,7 @@ template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
-  constexpr int FM = TM / 32, FN = TN / 32;
+  constexpr int FM = TM / MI, FN = TN / MI;
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   using LoadA = TileLoader<BM, AK, NW>;
   using LoadB = TileLoader<BN, BKM, NW>;
@@ -194,13 +205,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   const int tile_n = in_band / band_h;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  f32x16 acc[FN][FM];
+  acc_t acc[FN][FM];
 #pragma unroll
   for (int i = 0; i < FN; ++i)
 #pragma unroll
     for (int j = 0; j < FM; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < NACC; ++e) acc[i][j][e] = 0.f;
 
   int total = 0;
   for (int s = 0; s < p.nseg; ++s) total += p.K[s] / BK;
@@ -214,36 +225,78 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
+  // Software-pipelined K loop: operand fragments are double-buffered in registers; the barrier that
+  // hands over to the next stage sits before the last MFMA group of the current one, so the matrix
+  // pipe stays busy while the first fragments of the next stage are fetched from LDS.
+  constexpr int KK = BK / KSTEP;
+  static_assert(NS == 2, "the hand-over below is written for a two-stage ring");
+  bf16x8 fa[2][FM], fb[2][FN];
+  {
+    const char* ta = smem;
+    const char* tb = ta + A_BYTES;
+#pragma unroll
+    for (int j = 0; j < FM; ++j) fa[0][j] = read_frag<BM, AK>(ta, wave_m * TM + j * MI, 0, lane);
+#pragma unroll
+    for (int i = 0; i < FN; ++i) fb[0][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, 0, lane);
+  }
   for (int t = 0; t < total; ++t) {
     cur.issue_next(p, smem + ((t + NS - 1) % NS) * STAGE, wave, m0, n0, lane);
     const char* ta = smem + (t % NS) * STAGE;
     const char* tb = ta + A_BYTES;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[FM], fb[FN];
+    for (int kk = 0; kk < KK; ++kk) {
+      const int cb = kk & 1, nb = cb ^ 1;
+      if (kk + 1 < KK) {
 #pragma unroll
-      for (int j = 0; j < FM; ++j) fa[j] = read_frag<BM, AK>(ta, wave_m * TM + j * 32, kk, lane);
+        for (int j = 0; j < FM; ++j) fa[nb][j] = read_frag<BM, AK>(ta, wave_m * TM + j * MI, kk + 1, lane);
 #pragma unroll
-      for (int i = 0; i < FN; ++i) fb[i] = read_frag<BN, BKM>(tb, wave_n * TN + i * 32, kk, lane);
+        for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, kk + 1, lane);
+      } else {
+        // all of this wave's reads of stage t are in registers; stage t+1 must have landed
+        if (t + NS - 1 < total) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (t + 1 < total) {
+          const char* na = smem + ((t + 1) % NS) * STAGE;
+          const char* nbp = na + A_BYTES;
+#pragma unroll
+          for (int j = 0; j < FM; ++j) fa[nb][j] = read_frag<BM, AK>(na, wave_m * TM + j * MI, 0, lane);
+#pragma unroll
+          for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(nbp, wave_n * TN + i * MI, 0, lane);
+        }
+      }
 #pragma unroll
       for (int i = 0; i < FN; ++i)
 #pragma unroll
         for (int j = 0; j < FM; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma(fb[cb][i], fa[cb][j], acc[i][j]);
+#pragma unroll
+      for (int q = 0; q < FM + FN; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN) / (FM + FN), 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, AK && BKM ? 1 : 2, 0);      // DS read
+      }
     }
-    // stage t+1 must have landed; the NS-2 younger groups may still be in flight
-    if (t + NS - 1 < total) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
   }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
   // Epilogue through LDS: each wave owns a [TM][64] bf16 staging area per 64 columns of its tile
   // (128 bytes per row, chunk c of row m stored at c ^ ((m >> 1) & 7)), filled from the accumulator
   // layout (8 bytes per lane) and drained row-contiguously (16 bytes per lane, 8 lanes per row).
   static_assert(TN % 64 == 0, "staging layout assumes 128-byte rows");
   char* stg = smem + wave * (TM * 128);
-  const int lm = lane & 31, lh = lane >> 5;
+  const int lm = lane & (MI - 1), lq = lane / MI;
   const int rrow = lane >> 3, rpc = lane & 7;
+  constexpr int TPB = 64 / MI;      // MFMA blocks per 64 staged columns
+  constexpr int NG = NACC / 4;      // 4-column groups a lane holds per MFMA block
+  // column (within the 64 staged ones) of group g of block i for this lane
+  auto stg_off = [&](int j, int i, int g) {
+    const int row = j * MI + lm;
+    const int n = i * MI + (MI == 32 ? g * 8 + lq * 4 : lq * 4);
+    return row * 128 + ((((n >> 3) ^ ((row >> 1) & 7)) << 4) | ((n & 4) << 1));
+  };
 #pragma unroll
   for (int nb = 0; nb < TN / 64; ++nb) {
     const int nbase = n0 + wave_n * TN + nb * 64;
@@ -261,26 +314,24 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
 #pragma unroll
       for (int j = 0; j < FM; ++j)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TPB; ++i)
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int row = j * 32 + lm, c = i * 4 + g;
-            const bf16x4 v = *reinterpret_cast<const bf16x4*>(stg + row * 128 + ((c ^ ((row >> 1) & 7)) << 4) + lh * 8);
+          for (int g = 0; g < NG; ++g) {
+            const bf16x4 v = *reinterpret_cast<const bf16x4*>(stg + stg_off(j, i, g));
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[nb * 2 + i][j][g * 4 + e] += (float)v[e];
+            for (int e = 0; e < 4; ++e) acc[nb * TPB + i][j][g * 4 + e] += (float)v[e];
           }
     }
 #pragma unroll
     for (int j = 0; j < FM; ++j)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TPB; ++i)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int row = j * 32 + lm, c = i * 4 + g;
+        for (int g = 0; g < NG; ++g) {
           bf16x4 o;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[nb * 2 + i][j][g * 4 + e];
-          *reinterpret_cast<bf16x4*>(stg + row * 128 + ((c ^ ((row >> 1) & 7)) << 4) + lh * 8) = o;
+          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[nb * TPB + i][j][g * 4 + e];
+          *reinterpret_cast<bf16x4*>(stg + stg_off(j, i, g)) = o;
         }
 #pragma unroll
     for (int t = 0; t < TM / 8; ++t) {
