@@ -16,8 +16,9 @@
 //                                  c ^ ((r / (16/CPR)) & (CPR-1)), so 16 consecutive rows reading
 //                                  one logical chunk touch 16 different 16-byte bank groups.
 //   mn-major tile [BK k][R mn]   : R/8 chunks per k-row; chunk c of k-row k sits at
-//                                  c ^ (((k & 3) << 2) & (R/8 - 1)): the 4 k-rows x 64 B of a
-//                                  transposed read fall in 4 different 64-byte groups.
+//                                  c ^ ((((k & 3) << 2) | (((k >> 3) & 1) << 1)) & (R/8 - 1)): the
+//                                  8 k-rows x 32 B that 32 lanes of a transposed read touch fall in
+//                                  8 different 32-byte bank groups.
 // MFMA roles: the N-side operand feeds MFMA "A" (row index i), the M-side operand feeds MFMA
 // "B" (column index j), so a lane ends up with 4 consecutive n for one m.  The epilogue passes
 // the tile through LDS so that global stores (and residual loads) are 16 bytes per lane along
@@ -72,10 +73,18 @@ struct TileLoader {
   static constexpr int RPW = 16 / CPRK;             // k-major rows per 256-byte bank window
   static constexpr int CPR = R / 8;                 // chunks per k-row (mn-major)
   static constexpr int RPI = KMAJOR ? 1024 / (BK * 2) : 1024 / (R * 2);  // tile rows per instruction
-  // swizzle variants a lane needs across its instructions
-  static constexpr int NVAR = KMAJOR ? (RPI >= 16 ? 1 : 16 / RPI) : (RPI >= 4 ? 1 : 4 / RPI);
+  // k-major: swizzle variants a lane needs across its instructions (precomputed offsets);
+  // mn-major: the chunk swizzle is applied per instruction from (row part, chunk, k-row in instr).
+  static constexpr int NVAR = KMAJOR ? (RPI >= 16 ? 1 : 16 / RPI) : 1;
   static_assert(PER_WAVE % NVAR == 0, "swizzle variant must not depend on the wave index");
   uint32_t voff[NVAR];
+  int pc, kq;
+
+  // chunk XOR of k-row k of an mn-major tile: the rows k..k+3 (bits 2-3) and k+8.. (bit 1) that a
+  // 32-lane transposed read touches fall in 8 different 32-byte bank groups.
+  static __device__ __forceinline__ int mn_swz(int k) {
+    return (((k & 3) << 2) | (((k >> 3) & 1) << 1)) & (CPR - 1);
+  }
 
   __device__ __forceinline__ void init(int lane, int64_t ld) {
     if constexpr (KMAJOR) {
@@ -87,12 +96,9 @@ struct TileLoader {
         voff[v] = (uint32_t)((lane / CPRK) * ld * 2 + (c << 4));
       }
     } else {
-#pragma unroll
-      for (int v = 0; v < NVAR; ++v) {
-        const int krow = v * RPI + lane / CPR;  // k-row modulo 4
-        const int c = (lane % CPR) ^ (((krow & 3) << 2) & (CPR - 1));
-        voff[v] = (uint32_t)((lane / CPR) * ld * 2 + (c << 4));
-      }
+      kq = lane / CPR;
+      pc = lane % CPR;
+      voff[0] = (uint32_t)(kq * ld * 2);
     }
   }
 
@@ -103,8 +109,10 @@ struct TileLoader {
       const int j = wave * PER_WAVE + i;
       const uint32_t soff = KMAJOR ? (uint32_t)(((int64_t)RPI * j * ld + k0) * 2)
                                    : (uint32_t)(((int64_t)(k0 + j * RPI) * ld) * 2);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, voff[i % NVAR],
-                                               soff, 0, 0);
+      uint32_t vo;
+      if constexpr (KMAJOR) vo = voff[i % NVAR];
+      else vo = voff[0] + (uint32_t)((pc ^ mn_swz(j * RPI + kq)) << 4);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, vo, soff, 0, 0);
     }
   }
 };
@@ -122,7 +130,7 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row0, int kk, 
     const int grp = lane >> 4, s = lane & 15, e = s >> 2, g = s & 3;
     const int col = MI == 32 ? row0 + ((grp & 1) << 4) + (g << 2) : row0 + (g << 2);
     const int krow = MI == 32 ? kk * 16 + ((grp >> 1) << 3) + e : kk * 32 + (grp << 3) + e;
-    const int f = ((krow & 3) << 2) & (CPR - 1);  // same for krow and krow + 4
+    const int f = (((krow & 3) << 2) | (((krow >> 3) & 1) << 1)) & (CPR - 1);  // same for krow and krow + 4
     const char* p0 = tile + krow * (R * 2) + ((((col >> 3) ^ f) << 4) | ((col & 7) << 1));
     bf16x8 v;
     v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p0));
