@@ -95,15 +95,35 @@ __device__ __forceinline__ bf16x8 pack_slots(const f32x16& a, int first) {
   return v;
 }
 
+// Causal mask for a score tile held in the "lane owns one query (or key) column" accumulator
+// layout: register r of 32-row block i holds row i*32 + 8*(r/4) + 4*(lane/32) + r%4.  `lim` is the
+// largest row offset this lane may keep (computed by the caller with the 4*(lane/32) folded in);
+// rows above it get `fill`.  The empty volatile asm keeps the compiler from turning the caller's
+// wave-uniform `if (diagonal tile)` into per-element selects executed on every tile.
+template <int NBLK>
+__device__ __forceinline__ void mask_rows_above(f32x16 (&s)[NBLK], int lim, float fill) {
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (i * 32 + ((r >> 2) << 3) + (r & 3) > lim) s[i][r] = fill;
+}
+
 // ------------------------------------------------------------------------------------------
 // Forward.  Workgroup = 4 waves = 128 query rows of one (batch, query head); wave = 32 rows.
+// The softmax is VALU-bound next to the MFMA work, so the per-tile VALU count is kept minimal:
+// the 1/sqrt(dh)*log2(e) scale is folded into the exp2 argument with one FMA, the causal mask runs
+// only on diagonal tiles, and the running maximum is only raised (and O and the row sum rescaled)
+// when some row's maximum grew by more than 2^8 - P then stays below 256, well inside bf16, and
+// the final O / rowsum is unchanged because both carry the same stale reference.
 // ------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict__ q,
-                                                       const bf16_t* __restrict__ k,
-                                                       const bf16_t* __restrict__ v,
-                                                       bf16_t* __restrict__ o, float* __restrict__ lse,
-                                                       int S, int Hq, int Hkv, float scale_log2) {
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ q,
+                                                          const bf16_t* __restrict__ k,
+                                                          const bf16_t* __restrict__ v,
+                                                          bf16_t* __restrict__ o, float* __restrict__ lse,
+                                                          int S, int Hq, int Hkv, float scale_log2) {
   using Tile = RowTile<64, DH, 4>;
   constexpr int STAGE = 2 * Tile::BYTES;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -125,7 +145,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
   for (int t = 0; t < DH / 32; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
-  float m = -INFINITY, lsum = 0.f;
+  float m = -INFINITY, lsum = 0.f;   // m: reference exponent in scaled log2 units
 
   const bf16_t* kb = k + (int64_t)b * S * ldk + (int64_t)hk * DH;
   const bf16_t* vb = v + (int64_t)b * S * ldk + (int64_t)hk * DH;
@@ -146,59 +166,53 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
   for (int t = 0; t < nkv; ++t) {
     if (t + 1 < nkv) issue_tile(t + 1, stage ^ 1);
     const int kv0 = t * 64;
-    if (kv0 <= qw + 31) {
-      const char* tk = smem + stage * STAGE;
-      const char* tv = tk + Tile::BYTES;
-      f32x16 s[2];
+    const char* tk = smem + stage * STAGE;
+    const char* tv = tk + Tile::BYTES;
+    f32x16 s[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[i][e] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk)
 #pragma unroll
       for (int i = 0; i < 2; ++i)
+        s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tk, i * 32, kk, lane), qf[kk], s[i], 0, 0, 0);
+    // keys after the query (only on tiles that reach past this wave's first row; a tile that lies
+    // entirely after the wave's rows is masked out completely and contributes exact zeros)
+    if (kv0 + 63 > qw) mask_rows_above<2>(s, qw + lq - kv0 - (half << 2), -INFINITY);
+    float mx = s[0][0];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s[i][e] = 0.f;
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int kk = 0; kk < DH / 16; ++kk)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-          s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tk, i * 32, kk, lane), qf[kk], s[i], 0, 0, 0);
-      const bool need_mask = kv0 + 63 > qw;
-      const int qi = qw + lq;
-      float mx = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float val = s[i][r] * scale_log2;
-          if (need_mask) {
-            const int kvi = kv0 + i * 32 + ((r >> 2) << 3) + (half << 2) + (r & 3);
-            if (kvi > qi) val = -INFINITY;
-          }
-          s[i][r] = val;
-          mx = fmaxf(mx, val);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[i][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+    if (__builtin_amdgcn_ballot_w64(mx > m + 8.0f) != 0) {
       const float m_new = fmaxf(m, mx);
       const float alpha = fast_exp2(m - m_new);
-      float psum = 0.f;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float pv = fast_exp2(s[i][r] - m_new);
-          s[i][r] = pv;
-          psum += pv;
-        }
-      lsum = lsum * alpha + psum;
+      lsum *= alpha;
       m = m_new;
 #pragma unroll
       for (int t2 = 0; t2 < DH / 32; ++t2)
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[t2][e] *= alpha;
+    }
+    float psum = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 pf = pack_slots(s[ks >> 1], (ks & 1) * 8);
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int t2 = 0; t2 < DH / 32; ++t2)
-          oacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tv, t2 * 32, ks * 16, lane), pf, oacc[t2], 0, 0, 0);
+      for (int r = 0; r < 16; ++r) {
+        const float pv = fast_exp2(__builtin_fmaf(s[i][r], scale_log2, -m));
+        s[i][r] = pv;
+        psum += pv;
       }
+    lsum += psum;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const bf16x8 pf = pack_slots(s[ks >> 1], (ks & 1) * 8);
+#pragma unroll
+      for (int t2 = 0; t2 < DH / 32; ++t2)
+        oacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tv, t2 * 32, ks * 16, lane), pf, oacc[t2], 0, 0, 0);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -250,7 +264,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restric
 // dQ.  Same decomposition as the forward: workgroup = 128 query rows of one (batch, head).
 // ------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
     bf16_t* __restrict__ dq, int S, int Hq, int Hkv, float scale) {
@@ -298,40 +312,32 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
   for (int t = 0; t < nkv; ++t) {
     if (t + 1 < nkv) issue_tile(t + 1, stage ^ 1);
     const int kv0 = t * 64;
-    if (kv0 <= qw + 31) {
-      const char* tk = smem + stage * STAGE;
-      const char* tv = tk + Tile::BYTES;
-      f32x16 s[2], dp[2];
+    const char* tk = smem + stage * STAGE;
+    const char* tv = tk + Tile::BYTES;
+    // two 32-key halves per tile: keeps the live score registers at 32 so two waves fit per SIMD
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
+      f32x16 s[1], dp;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { s[i][e] = 0.f; dp[i][e] = 0.f; }
+      for (int e = 0; e < 16; ++e) { s[0][e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
-      for (int kk = 0; kk < DH / 16; ++kk)
+      for (int kk = 0; kk < DH / 16; ++kk) {
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tk, i * 32, kk, lane), qf[kk], s[0], 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tv, i * 32, kk, lane), dof[kk], dp, 0, 0, 0);
+      }
+      // P^T = exp2(s*c - lse); keys after the query get exp2(-inf) = 0
+      if (kv0 + i * 32 + 31 > qw) mask_rows_above<1>(s, qw + lq - kv0 - i * 32 - (half << 2), -INFINITY);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          s[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tk, i * 32, kk, lane), qf[kk], s[i], 0, 0, 0);
-          dp[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tv, i * 32, kk, lane), dof[kk], dp[i], 0, 0, 0);
-        }
-      const bool need_mask = kv0 + 63 > qw;
-      const int qi = qw + lq;
+      for (int r = 0; r < 16; ++r) {
+        const float pv = fast_exp2(__builtin_fmaf(s[0][r], scale_log2, -lse2));
+        s[0][r] = pv * (dp[r] - dl);  // dS^T
+      }
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float pv = fast_exp2(s[i][r] * scale_log2 - lse2);
-          if (need_mask) {
-            const int kvi = kv0 + i * 32 + ((r >> 2) << 3) + (half << 2) + (r & 3);
-            if (kvi > qi) pv = 0.f;
-          }
-          s[i][r] = pv * (dp[i][r] - dl);  // dS^T
-        }
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 df = pack_slots(s[ks >> 1], (ks & 1) * 8);
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 df = pack_slots(s[0], ks * 8);
 #pragma unroll
         for (int t2 = 0; t2 < DH / 32; ++t2)
-          acc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tk, t2 * 32, ks * 16, lane), df, acc[t2], 0, 0, 0);
+          acc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tk, t2 * 32, i * 32 + ks * 16, lane), df, acc[t2], 0, 0, 0);
       }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -351,39 +357,43 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// dK, dV.  Workgroup = 4 waves = 128 keys of one (batch, kv head); wave = 32 keys.  Streams the
-// Q and dO tiles (64 query rows) of every query head of the group from the diagonal downwards.
+// dK or dV (template flag).  Workgroup = 4 waves = 128 keys of one (batch, kv head); wave = 32 keys.
+// Streams the Q and dO tiles (64 query rows) of every query head of the group from the diagonal
+// downwards.  One kernel holding both accumulators needs 192 registers of state and runs one wave
+// per SIMD at 30 % MFMA utilisation (measured); computing dV (S, dV^T products) and dK (S, dP, dK^T
+// products) in two launches costs one more S product but each fits two waves per SIMD, so one wave's
+// exp/dS arithmetic runs under the other's MFMAs.
 // ------------------------------------------------------------------------------------------
-template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
+template <int DH, bool WANT_DV>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
-    bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int S, int Hq, int Hkv, float scale) {
+    bf16_t* __restrict__ dout, int S, int Hq, int Hkv, float scale) {
   using Tile = RowTile<64, DH, 4>;
   constexpr int STAGE = 2 * Tile::BYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int kt = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int kt = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;   // low key tiles have the most query tiles: first
   const int G = Hq / Hkv;
   const int kv0 = kt * 128, kvw = kv0 + wave * 32;
   const int lk = lane & 31, half = lane >> 5;
   const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
   const float scale_log2 = scale * kLog2e;
 
-  bf16x8 kf[DH / 16], vf[DH / 16];
+  bf16x8 kf[DH / 16], vf[WANT_DV ? 1 : DH / 16];
   {
     const int64_t off = ((int64_t)b * S + kvw + lk) * ldk + (int64_t)hk * DH + half * 8;
 #pragma unroll
     for (int kk = 0; kk < DH / 16; ++kk) {
       kf[kk] = *reinterpret_cast<const bf16x8*>(k + off + kk * 16);
-      vf[kk] = *reinterpret_cast<const bf16x8*>(v + off + kk * 16);
+      if constexpr (!WANT_DV) vf[kk] = *reinterpret_cast<const bf16x8*>(v + off + kk * 16);
     }
   }
-  f32x16 dva[DH / 32], dka[DH / 32];
+  f32x16 acc[DH / 32];
 #pragma unroll
   for (int t = 0; t < DH / 32; ++t)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { dva[t][e] = 0.f; dka[t][e] = 0.f; }
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
 
   const int first_qt = kv0 / 64, nq = S / 64 - first_qt, niter = G * nq;
   const uint32_t q_bytes = (uint32_t)((((int64_t)S - 1) * ldq + DH) * 2);
@@ -398,7 +408,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
       const int64_t sidx = ((int64_t)b * Hq + h) * S + qrow + lane;
       float* stat = reinterpret_cast<float*>(st + 2 * Tile::BYTES);
       stat[lane] = lse[sidx] * kLog2e;
-      stat[64 + lane] = delta[sidx];
+      if constexpr (!WANT_DV) stat[64 + lane] = delta[sidx];
     }
   };
   issue_tile(0, 0);
@@ -411,62 +421,64 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
     const char* tq = smem + stage * STAGE;
     const char* tdo = tq + Tile::BYTES;
     const float* stat = reinterpret_cast<const float*>(tq + 2 * Tile::BYTES);
+    // queries before the key are masked: P = 0 for query rows below  kvw + lk - qrow
+    const bool diag = qrow < kvw + 31;
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
-      const int qb = qrow + qs * 32;
-      if (qb + 31 >= kvw) {
-        f32x16 s, dp;
+      // S[q][kv] (and dP[q][kv]) for 32 queries: lane owns key kvw + lk, queries along registers
+      f32x16 s, dp;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
-        for (int kk = 0; kk < DH / 16; ++kk) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tq, qs * 32, kk, lane), kf[kk], s, 0, 0, 0);
+      for (int kk = 0; kk < DH / 16; ++kk) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tq, qs * 32, kk, lane), kf[kk], s, 0, 0, 0);
+        if constexpr (!WANT_DV)
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tdo, qs * 32, kk, lane), vf[kk], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int ql = qs * 32 + g * 8 + half * 4;
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + ql);
+        f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (!WANT_DV) d4 = *reinterpret_cast<const f32x4*>(stat + 64 + ql);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = g * 4 + e;
+          const float pv = fast_exp2(__builtin_fmaf(s[r], scale_log2, -l4[e]));
+          if constexpr (WANT_DV) s[r] = pv; else s[r] = pv * (dp[r] - d4[e]);   // P or dS
         }
-        const bool need_mask = qb < kvw + 31;
-        const int kvi = kvw + lk;
+      }
+      if (diag) {
+        asm volatile("" ::: "memory");
+        const int first_ok = kvw + lk - qrow - (half << 2);   // smallest unmasked row offset for this lane
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int ql = qs * 32 + g * 8 + half * 4;
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + ql);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 64 + ql);
+        for (int r = 0; r < 16; ++r)
+          if (qs * 32 + ((r >> 2) << 3) + (r & 3) < first_ok) s[r] = 0.f;
+      }
+      // dV^T[d][kv] += dO^T[d][q] P[q][kv]   or   dK^T[d][kv] += Q^T[d][q] dS[q][kv]
+      const char* tsrc = WANT_DV ? tdo : tq;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = g * 4 + e;
-            float pv = fast_exp2(s[r] * scale_log2 - l4[e]);
-            if (need_mask && kvi > qrow + ql + e) pv = 0.f;
-            s[r] = pv;
-            dp[r] = pv * (dp[r] - d4[e]);
-          }
-        }
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 pf = pack_slots(s, ks * 8);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-          const bf16x8 pf = pack_slots(s, ks * 8), df = pack_slots(dp, ks * 8);
-#pragma unroll
-          for (int t2 = 0; t2 < DH / 32; ++t2) {
-            dva[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tdo, t2 * 32, qs * 32 + ks * 16, lane), pf, dva[t2], 0, 0, 0);
-            dka[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tq, t2 * 32, qs * 32 + ks * 16, lane), df, dka[t2], 0, 0, 0);
-          }
-        }
+        for (int t2 = 0; t2 < DH / 32; ++t2)
+          acc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tsrc, t2 * 32, qs * 32 + ks * 16, lane), pf, acc[t2], 0, 0, 0);
       }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     stage ^= 1;
   }
+  const float oscale = WANT_DV ? 1.0f : scale;
   const int64_t off = ((int64_t)b * S + kvw + lk) * ldk + (int64_t)hk * DH + half * 4;
 #pragma unroll
   for (int t2 = 0; t2 < DH / 32; ++t2)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      bf16x4 ok, ov;
+      bf16x4 ov;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        ok[e] = (bf16_t)(dka[t2][g * 4 + e] * scale);
-        ov[e] = (bf16_t)dva[t2][g * 4 + e];
-      }
-      *reinterpret_cast<bf16x4*>(dk + off + t2 * 32 + g * 8) = ok;
-      *reinterpret_cast<bf16x4*>(dv + off + t2 * 32 + g * 8) = ov;
+      for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(acc[t2][g * 4 + e] * oscale);
+      *reinterpret_cast<bf16x4*>(dout + off + t2 * 32 + g * 8) = ov;
     }
 }
 
@@ -519,13 +531,19 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
   static bool once = false;
   if (!once) {
     if (int rc = set_lds(attn_bwd_dq_kernel<DH>, lds_dq)) return rc;
-    if (int rc = set_lds(attn_bwd_dkdv_kernel<DH>, lds_kv)) return rc;
+    if (int rc = set_lds(attn_bwd_dkv_kernel<DH, true>, lds_kv)) return rc;
+    if (int rc = set_lds(attn_bwd_dkv_kernel<DH, false>, lds_kv)) return rc;
     once = true;
   }
-  hipLaunchKernelGGL(attn_bwd_dkdv_kernel<DH>, dim3((unsigned)(S / 128), (unsigned)Hkv, (unsigned)B), dim3(256),
-                     lds_kv, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)d_o, lse,
-                     (const float*)delta, (bf16_t*)dk, (bf16_t*)dv, (int)S, (int)Hq, (int)Hkv, scale);
-  if (int rc = check_launch("attention_backward(dk,dv)")) return rc;
+  const dim3 kv_grid((unsigned)(S / 128), (unsigned)Hkv, (unsigned)B);
+  hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, true>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
+                     (const bf16_t*)v, (const bf16_t*)d_o, lse, (const float*)delta, (bf16_t*)dv, (int)S, (int)Hq,
+                     (int)Hkv, scale);
+  if (int rc = check_launch("attention_backward(dv)")) return rc;
+  hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, false>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
+                     (const bf16_t*)v, (const bf16_t*)d_o, lse, (const float*)delta, (bf16_t*)dk, (int)S, (int)Hq,
+                     (int)Hkv, scale);
+  if (int rc = check_launch("attention_backward(dk)")) return rc;
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3((unsigned)(S / 128), (unsigned)Hq, (unsigned)B), dim3(256),
                      lds_dq, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)d_o, lse,
                      (const float*)delta, (bf16_t*)dq, (int)S, (int)Hq, (int)Hkv, scale);
