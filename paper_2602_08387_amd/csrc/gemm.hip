@@ -224,12 +224,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   int total = 0;
   for (int s = 0; s < p.nseg; ++s) total += p.K[s] / BK;
 
-  // Load cursor: runs NS-1 K-steps ahead of the compute cursor, across segment boundaries.
+  // Load cursor: runs two K-steps ahead of the compute cursor, across segment boundaries.
   LoadCursor<BM, BN, NW, AK, BKM> cur;
   cur.open(p, 0, m0, n0, lane);
-#pragma unroll
-  for (int i = 0; i < NS - 1; ++i) cur.issue_next(p, smem + i * STAGE, wave, m0, n0, lane);
-  if (total >= NS - 1) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
+  cur.issue_next(p, smem, wave, m0, n0, lane);
+  cur.issue_next(p, smem + STAGE, wave, m0, n0, lane);
+  if (total >= 2) wait_vmcnt<LPW>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
@@ -248,7 +248,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
     for (int i = 0; i < FN; ++i) fb[0][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, 0, lane);
   }
   for (int t = 0; t < total; ++t) {
-    cur.issue_next(p, smem + ((t + NS - 1) % NS) * STAGE, wave, m0, n0, lane);
     const char* ta = smem + (t % NS) * STAGE;
     const char* tb = ta + A_BYTES;
 #pragma unroll
@@ -261,10 +260,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
         for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, kk + 1, lane);
       } else {
         // all of this wave's reads of stage t are in registers; stage t+1 must have landed
-        if (t + NS - 1 < total) wait_vmcnt<(NS - 2) * LPW>(); else wait_vmcnt<0>();
+        wait_vmcnt<0>();   // the only loads in flight are those of stage t+1, issued one K-step ago
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+        // every wave now holds its last fragments of stage t in registers: refill that stage with
+        // step t+2 right away, so the loads get a whole K-step to land (measured global -> LDS
+        // latency under load: about 1800 cycles against a K-step of about 3000)
+        cur.issue_next(p, smem + (t % NS) * STAGE, wave, m0, n0, lane);
         if (t + 1 < total) {
           const char* na = smem + ((t + 1) % NS) * STAGE;
           const char* nbp = na + A_BYTES;
