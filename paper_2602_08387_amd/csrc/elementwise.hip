@@ -149,14 +149,24 @@ __global__ __launch_bounds__(64 * kRmsBwdWaves) void rmsnorm_bwd_kernel(
   }
 }
 
-__global__ void colsum_partials_kernel(const float* __restrict__ partial, int nrows, int D,
-                                       bf16_t* out, int accumulate) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= D) return;
+// Column sums of the per-block partial rows: 256 threads = 32 columns x 8 row groups, folded through LDS.
+__global__ __launch_bounds__(256) void colsum_partials_kernel(const float* __restrict__ partial, int nrows, int D,
+                                                              bf16_t* out, int accumulate) {
+  __shared__ float red[8][33];
+  const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cl;
   float s = 0.f;
-  for (int r = 0; r < nrows; ++r) s += partial[(int64_t)r * D + c];
-  if (accumulate) s += (float)out[c];
-  out[c] = (bf16_t)s;
+  if (c < D)
+    for (int r = rg; r < nrows; r += 8) s += partial[(int64_t)r * D + c];
+  red[rg][cl] = s;
+  __syncthreads();
+  if (rg == 0 && c < D) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) t += red[g][cl];
+    if (accumulate) t += (float)out[c];
+    out[c] = (bf16_t)t;
+  }
 }
 
 static int rms_bwd_blocks(int64_t T) {
@@ -194,7 +204,7 @@ int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, cons
 #undef RMS_BWD
   int rc = check_launch("rmsnorm_backward");
   if (rc) return rc;
-  hipLaunchKernelGGL(colsum_partials_kernel, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, st,
+  hipLaunchKernelGGL(colsum_partials_kernel, dim3((unsigned)((D + 31) / 32)), dim3(256), 0, st,
                      (const float*)workspace, nb, (int)D, (bf16_t*)dgamma, accumulate);
   return check_launch("rmsnorm_backward(dgamma)");
 }
