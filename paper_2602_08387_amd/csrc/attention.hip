@@ -234,13 +234,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
 }
 
 // ------------------------------------------------------------------------------------------
-// delta[b, h, q] = sum_d dO[q, h, d] * O[q, h, d]
+// delta[b, h, q] = sum_d dO[q, h, d] * O[q, h, d], and lse2 = lse * log2(e) (the exponent reference
+// in the units the backward kernels' exp2 works in), both [B, Hq, S] fp32.
 // ------------------------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restrict__ o,
                                                          const bf16_t* __restrict__ d_o,
-                                                         float* __restrict__ delta, int64_t rows,
-                                                         int S, int Hq) {
+                                                         const float* __restrict__ lse,
+                                                         float* __restrict__ delta, float* __restrict__ lse2,
+                                                         int64_t rows, int S, int Hq) {
   constexpr int LPR = DH / 8;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = idx / LPR;  // row = (b*S + q)*Hq + h
@@ -257,6 +259,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restric
     const int h = (int)(row % Hq);
     const int64_t b = tok / S, qi = tok % S;
     delta[(b * Hq + h) * S + qi] = acc;
+    lse2[(b * Hq + h) * S + qi] = lse[(b * Hq + h) * S + qi] * kLog2e;
   }
 }
 
@@ -367,7 +370,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 template <int DH, bool WANT_DV>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
+    const bf16_t* __restrict__ d_o, const float* __restrict__ lse2, const float* __restrict__ delta,
     bf16_t* __restrict__ dout, int S, int Hq, int Hkv, float scale) {
   using Tile = RowTile<64, DH, 4>;
   constexpr int STAGE = 2 * Tile::BYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
@@ -404,12 +407,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     char* st = smem + stage * STAGE;
     Tile::issue(attn_rsrc(q + base + (int64_t)qrow * ldq, q_bytes - skip), st, wave, lane, ldq);
     Tile::issue(attn_rsrc(d_o + base + (int64_t)qrow * ldq, q_bytes - skip), st + Tile::BYTES, wave, lane, ldq);
-    if (wave == 0) {
-      const int64_t sidx = ((int64_t)b * Hq + h) * S + qrow + lane;
-      float* stat = reinterpret_cast<float*>(st + 2 * Tile::BYTES);
-      stat[lane] = lse[sidx] * kLog2e;
-      if constexpr (!WANT_DV) stat[64 + lane] = delta[sidx];
-    }
+    // the 64 lse2 (and delta) values of the tile take the same asynchronous global -> LDS path, 4 bytes
+    // per lane: a register round trip here would make the wave wait for the tile loads as well
+    const int64_t sidx = ((int64_t)b * Hq + h) * S + qrow;
+    if (wave == 0)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(attn_rsrc(lse2 + sidx, 256), (LDS_PTR(void))(st + 2 * Tile::BYTES), 4,
+                                               (uint32_t)lane * 4, 0, 0, 0);
+    if (!WANT_DV && wave == 1)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(attn_rsrc(delta + sidx, 256), (LDS_PTR(void))(st + 2 * Tile::BYTES + 256),
+                                               4, (uint32_t)lane * 4, 0, 0, 0);
   };
   issue_tile(0, 0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -512,7 +518,7 @@ int launch_attention_fwd(const void* q, const void* k, const void* v, int64_t B,
 }
 
 size_t attention_bwd_workspace(int64_t B, int64_t S, int64_t Hq, int64_t, int64_t) {
-  return (size_t)B * Hq * S * sizeof(float);
+  return 2 * (size_t)B * Hq * S * sizeof(float);   // delta and lse * log2(e)
 }
 
 template <int DH>
@@ -520,10 +526,11 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
                   const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, void* dq, void* dk,
                   void* dv, void* workspace, hipStream_t st) {
   float* delta = (float*)workspace;
+  float* lse2 = delta + B * Hq * S;
   const int64_t rows = B * S * Hq;
   const int64_t nthreads = rows * (DH / 8);
   hipLaunchKernelGGL(attn_delta_kernel<DH>, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, st,
-                     (const bf16_t*)o, (const bf16_t*)d_o, delta, rows, (int)S, (int)Hq);
+                     (const bf16_t*)o, (const bf16_t*)d_o, lse, delta, lse2, rows, (int)S, (int)Hq);
   if (int rc = check_launch("attention_backward(delta)")) return rc;
   const float scale = (float)(1.0 / sqrt((double)DH));
   const size_t lds_dq = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
@@ -537,11 +544,11 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
   }
   const dim3 kv_grid((unsigned)(S / 128), (unsigned)Hkv, (unsigned)B);
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, true>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
-                     (const bf16_t*)v, (const bf16_t*)d_o, lse, (const float*)delta, (bf16_t*)dv, (int)S, (int)Hq,
+                     (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dv, (int)S, (int)Hq,
                      (int)Hkv, scale);
   if (int rc = check_launch("attention_backward(dv)")) return rc;
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, false>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
-                     (const bf16_t*)v, (const bf16_t*)d_o, lse, (const float*)delta, (bf16_t*)dk, (int)S, (int)Hq,
+                     (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (int)S, (int)Hq,
                      (int)Hkv, scale);
   if (int rc = check_launch("attention_backward(dk)")) return rc;
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3((unsigned)(S / 128), (unsigned)Hq, (unsigned)B), dim3(256),
