@@ -400,8 +400,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 
   const int first_qt = kv0 / 64, nq = S / 64 - first_qt, niter = G * nq;
   const uint32_t q_bytes = (uint32_t)((((int64_t)S - 1) * ldq + DH) * 2);
-  auto issue_tile = [&](int it, int stage) {
-    const int h = hk * G + it / nq, qrow = (first_qt + it % nq) * 64;
+  // (head, query tile) of the tile to load next and of the tile being processed, advanced without
+  // divisions: the query tile runs first_qt .. S/64-1 for each of the G heads in turn
+  int ld_h = hk * G, ld_qt = first_qt, cur_qt = first_qt;
+  auto issue_tile = [&](int stage) {
+    const int h = ld_h, qrow = ld_qt * 64;
+    if (++ld_qt == S / 64) { ld_qt = first_qt; ++ld_h; }
     const int64_t base = ((int64_t)b * S) * ldq + (int64_t)h * DH;
     const uint32_t skip = (uint32_t)((int64_t)qrow * ldq * 2);
     char* st = smem + stage * STAGE;
@@ -417,13 +421,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
       __builtin_amdgcn_raw_ptr_buffer_load_lds(attn_rsrc(delta + sidx, 256), (LDS_PTR(void))(st + 2 * Tile::BYTES + 256),
                                                4, (uint32_t)lane * 4, 0, 0, 0);
   };
-  issue_tile(0, 0);
+  issue_tile(0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   int stage = 0;
   for (int it = 0; it < niter; ++it) {
-    if (it + 1 < niter) issue_tile(it + 1, stage ^ 1);
-    const int qrow = (first_qt + it % nq) * 64;
+    if (it + 1 < niter) issue_tile(stage ^ 1);
+    const int qrow = cur_qt * 64;
+    if (++cur_qt == S / 64) cur_qt = first_qt;
     const char* tq = smem + stage * STAGE;
     const char* tdo = tq + Tile::BYTES;
     const float* stat = reinterpret_cast<const float*>(tq + 2 * Tile::BYTES);
