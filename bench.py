@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=4096)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (the known-size dispatch that HBM byte "
+                         "counters of a profiler run are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU decoder-layer step; this build has no multi-GPU path "
@@ -90,6 +93,11 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)           # reads 1 GiB, writes 1 GiB
+        del src, dst
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -111,6 +111,21 @@ __device__ __forceinline__ void mask_rows_above(f32x16 (&s)[NBLK], int lim, floa
 }
 
 // ------------------------------------------------------------------------------------------
+// Workgroup -> work mapping shared by all kernels here.  Consecutive workgroup ids are dealt to the
+// eight XCDs in turn and every XCD has an L2 of its own, so all work on one (batch, kv head) pair is
+// given to ONE XCD (ids congruent mod 8) when the number of pairs is a multiple of 8: the K/V tiles
+// (forward, dQ) or Q/dO tiles (dK, dV) of that pair are then fetched into one L2 only, and the
+// workgroups that share them run side by side and walk them in the same order.  `j` counts the
+// position in the pair's own queue (heaviest first is the caller's business).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void split_block_id(int id, int npairs, int& j, int& pair) {
+  int per_xcd = npairs, xcd = 0, slot = id;
+  if ((npairs & 7) == 0) { per_xcd = npairs >> 3; xcd = id & 7; slot = id >> 3; }
+  j = slot / per_xcd;
+  pair = xcd * per_xcd + slot % per_xcd;
+}
+
+// ------------------------------------------------------------------------------------------
 // Forward.  Workgroup = 4 waves = 128 query rows of one (batch, query head); wave = 32 rows.
 // The softmax is VALU-bound next to the MFMA work, so the per-tile VALU count is kept minimal:
 // the 1/sqrt(dh)*log2(e) scale is folded into the exp2 argument with one FMA, the causal mask runs
@@ -123,13 +138,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
                                                           const bf16_t* __restrict__ k,
                                                           const bf16_t* __restrict__ v,
                                                           bf16_t* __restrict__ o, float* __restrict__ lse,
-                                                          int S, int Hq, int Hkv, float scale_log2) {
+                                                          int B, int S, int Hq, int Hkv, float scale_log2) {
   using Tile = RowTile<64, DH, 4>;
   constexpr int STAGE = 2 * Tile::BYTES;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const int hk = h / (Hq / Hkv);
+  int j, pair;
+  split_block_id((int)blockIdx.x, B * Hkv, j, pair);
+  const int G = Hq / Hkv, b = pair / Hkv, hk = pair % Hkv;
+  const int qt = S / 128 - 1 - j / G, h = hk * G + j % G;   // long rows (late query tiles) first
   const int q0 = qt * 128, qw = q0 + wave * 32;
   const int lq = lane & 31, half = lane >> 5;
   const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
@@ -270,13 +287,15 @@ template <int DH>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
-    bf16_t* __restrict__ dq, int S, int Hq, int Hkv, float scale) {
+    bf16_t* __restrict__ dq, int B, int S, int Hq, int Hkv, float scale) {
   using Tile = RowTile<64, DH, 4>;
   constexpr int STAGE = 2 * Tile::BYTES;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const int hk = h / (Hq / Hkv);
+  int j, pair;
+  split_block_id((int)blockIdx.x, B * Hkv, j, pair);
+  const int G = Hq / Hkv, b = pair / Hkv, hk = pair % Hkv;
+  const int qt = S / 128 - 1 - j / G, h = hk * G + j % G;   // long rows (late query tiles) first
   const int q0 = qt * 128, qw = q0 + wave * 32;
   const int lq = lane & 31, half = lane >> 5;
   const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
@@ -361,8 +380,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 
 // ------------------------------------------------------------------------------------------
 // dK or dV (template flag).  Workgroup = 4 waves = 128 keys of one (batch, kv head); wave = 32 keys.
-// Streams the Q and dO tiles (64 query rows) of every query head of the group from the diagonal
-// downwards.  One kernel holding both accumulators needs 192 registers of state and runs one wave
+// Streams the Q and dO tiles (64 query rows) of every query head of the group, from the last query
+// tile back to the diagonal.  One kernel holding both accumulators needs 192 registers of state and runs one wave
 // per SIMD at 30 % MFMA utilisation (measured); computing dV (S, dV^T products) and dK (S, dP, dK^T
 // products) in two launches costs one more S product but each fits two waves per SIMD, so one wave's
 // exp/dS arithmetic runs under the other's MFMAs.
@@ -371,13 +390,14 @@ template <int DH, bool WANT_DV>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ d_o, const float* __restrict__ lse2, const float* __restrict__ delta,
-    bf16_t* __restrict__ dout, int S, int Hq, int Hkv, float scale) {
+    bf16_t* __restrict__ dout, int B, int S, int Hq, int Hkv, float scale) {
   using Tile = RowTile<64, DH, 4>;
   constexpr int STAGE = 2 * Tile::BYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int kt = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;   // low key tiles have the most query tiles: first
-  const int G = Hq / Hkv;
+  int kt, pair;   // low key tiles have the most query tiles: first
+  split_block_id((int)blockIdx.x, B * Hkv, kt, pair);
+  const int G = Hq / Hkv, b = pair / Hkv, hk = pair % Hkv;
   const int kv0 = kt * 128, kvw = kv0 + wave * 32;
   const int lk = lane & 31, half = lane >> 5;
   const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
@@ -400,12 +420,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 
   const int first_qt = kv0 / 64, nq = S / 64 - first_qt, niter = G * nq;
   const uint32_t q_bytes = (uint32_t)((((int64_t)S - 1) * ldq + DH) * 2);
-  // (head, query tile) of the tile to load next and of the tile being processed, advanced without
-  // divisions: the query tile runs first_qt .. S/64-1 for each of the G heads in turn
-  int ld_h = hk * G, ld_qt = first_qt, cur_qt = first_qt;
+  // (query tile, head) of the tile to load next and of the tile being processed, advanced without
+  // divisions.  Every workgroup walks the query tiles from the LAST one down to its diagonal, all G
+  // heads of a tile in turn: workgroups of one pair that start together then read the same Q/dO
+  // tile at the same time, whatever their key tile, and share it in the L2.
+  int ld_g = 0, ld_qt = S / 64 - 1, cur_g = 0, cur_qt = S / 64 - 1;
   auto issue_tile = [&](int stage) {
-    const int h = ld_h, qrow = ld_qt * 64;
-    if (++ld_qt == S / 64) { ld_qt = first_qt; ++ld_h; }
+    const int h = hk * G + ld_g, qrow = ld_qt * 64;
+    if (++ld_g == G) { ld_g = 0; --ld_qt; }
     const int64_t base = ((int64_t)b * S) * ldq + (int64_t)h * DH;
     const uint32_t skip = (uint32_t)((int64_t)qrow * ldq * 2);
     char* st = smem + stage * STAGE;
@@ -428,7 +450,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
   for (int it = 0; it < niter; ++it) {
     if (it + 1 < niter) issue_tile(stage ^ 1);
     const int qrow = cur_qt * 64;
-    if (++cur_qt == S / 64) cur_qt = first_qt;
+    if (++cur_g == G) { cur_g = 0; --cur_qt; }
     const char* tq = smem + stage * STAGE;
     const char* tdo = tq + Tile::BYTES;
     const float* stat = reinterpret_cast<const float*>(tq + 2 * Tile::BYTES);
@@ -509,8 +531,8 @@ static int fwd_dh(const void* q, const void* k, const void* v, int64_t B, int64_
   static bool once = false;
   if (!once) { if (int rc = set_lds(attn_fwd_kernel<DH>, lds)) return rc; once = true; }
   const float scale_log2 = (float)(1.0 / sqrt((double)DH)) * kLog2e;
-  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((unsigned)(S / 128), (unsigned)Hq, (unsigned)B), dim3(256),
-                     lds, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse, (int)S,
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((unsigned)(S / 128 * Hq * B)), dim3(256),
+                     lds, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse, (int)B, (int)S,
                      (int)Hq, (int)Hkv, scale_log2);
   return check_launch("attention_forward");
 }
@@ -547,18 +569,18 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
     if (int rc = set_lds(attn_bwd_dkv_kernel<DH, false>, lds_kv)) return rc;
     once = true;
   }
-  const dim3 kv_grid((unsigned)(S / 128), (unsigned)Hkv, (unsigned)B);
+  const dim3 kv_grid((unsigned)(S / 128 * Hkv * B));
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, true>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
-                     (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dv, (int)S, (int)Hq,
+                     (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dv, (int)B, (int)S, (int)Hq,
                      (int)Hkv, scale);
   if (int rc = check_launch("attention_backward(dv)")) return rc;
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, false>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
-                     (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (int)S, (int)Hq,
+                     (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (int)B, (int)S, (int)Hq,
                      (int)Hkv, scale);
   if (int rc = check_launch("attention_backward(dk)")) return rc;
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3((unsigned)(S / 128), (unsigned)Hq, (unsigned)B), dim3(256),
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3((unsigned)(S / 128 * Hq * B)), dim3(256),
                      lds_dq, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)d_o, lse,
-                     (const float*)delta, (bf16_t*)dq, (int)S, (int)Hq, (int)Hkv, scale);
+                     (const float*)delta, (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale);
   return check_launch("attention_backward(dq)");
 }
 
