@@ -148,14 +148,17 @@ static int gemm_dgrad(int nseg, const void* const* dy, const void* const* w, con
   return launch_gemm(g, st);
 }
 // dw[N,K] (+)= dy[T,N]^T x[T,K]
-static int gemm_wgrad(const void* dy, const void* x, int64_t T, int64_t N, int64_t K, void* dw, int accumulate,
-                      hipStream_t st) {
+static GemmArgs wgrad_args(const void* dy, const void* x, int64_t T, int64_t N, int64_t K, void* dw, int accumulate) {
   GemmArgs g{};
   g.nseg = 1;
   g.seg[0] = {dy, x, N, K, (int)T};
   g.M = (int)N; g.N = (int)K; g.c = dw; g.ldc = K; g.r = nullptr; g.accumulate = accumulate;
   g.a_kmajor = false; g.b_kmajor = false;
-  return launch_gemm(g, st);
+  return g;
+}
+static int gemm_wgrad(const void* dy, const void* x, int64_t T, int64_t N, int64_t K, void* dw, int accumulate,
+                      hipStream_t st) {
+  return launch_gemm(wgrad_args(dy, x, T, N, K, dw, accumulate), st);
 }
 
 }  // namespace dl
@@ -229,21 +232,17 @@ int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* 
     const void* dys[1] = {dy}; const void* ws[1] = {w->w_down}; const int64_t ns[1] = {D};
     TRY(gemm_dgrad(1, dys, ws, ns, T, F, k.da_dg, st));
   }
-  TRY(gemm_wgrad(dy, s.a, T, D, F, dw->w_down, acc, st));
   TRY(launch_swiglu_bwd(s.g, s.u, k.da_dg, T * F, k.da_dg, k.du, st));
   {
     const void* dys[2] = {k.da_dg, k.du}; const void* ws[2] = {w->w_gate, w->w_up}; const int64_t ns[2] = {F, F};
     TRY(gemm_dgrad(2, dys, ws, ns, T, D, k.dh2, st));
   }
-  TRY(gemm_wgrad(k.da_dg, s.h2, T, F, D, dw->w_gate, acc, st));
-  TRY(gemm_wgrad(k.du, s.h2, T, F, D, dw->w_up, acc, st));
   TRY(launch_rmsnorm_bwd(s.y1, w->g_mlp, s.rstd2, k.dh2, dy, T, D, k.dy1, dw->g_mlp, acc, k.rms_ws, st));
   // y1 = x + o Wo^T
   {
     const void* dys[1] = {k.dy1}; const void* ws[1] = {w->wo}; const int64_t ns[1] = {D};
     TRY(gemm_dgrad(1, dys, ws, ns, T, QD, k.d_o, st));
   }
-  TRY(gemm_wgrad(k.dy1, s.o, T, D, QD, dw->wo, acc, st));
   TRY(launch_attention_bwd(s.q, s.k, s.v, s.o, k.d_o, s.lse, B, S, Hq, Hkv, dh, k.dq, k.dk, k.dv, k.attn_ws, st));
   TRY(launch_rope(k.dq, B, S, Hq, dh, cfg->rope_base, cfg->rope_layout, 1, st));
   TRY(launch_rope(k.dk, B, S, Hkv, dh, cfg->rope_base, cfg->rope_layout, 1, st));
@@ -252,10 +251,16 @@ int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* 
     const int64_t ns[3] = {QD, KD, KD};
     TRY(gemm_dgrad(3, dys, ws, ns, T, D, k.dh1, st));
   }
-  TRY(gemm_wgrad(k.dq, s.h1, T, QD, D, dw->wq, acc, st));
-  TRY(gemm_wgrad(k.dk, s.h1, T, KD, D, dw->wk, acc, st));
-  TRY(gemm_wgrad(k.dv, s.h1, T, KD, D, dw->wv, acc, st));
   TRY(launch_rmsnorm_bwd(x, w->g_attn, s.rstd1, k.dh1, k.dy1, T, D, dx, dw->g_attn, acc, k.rms_ws, st));
+  // All seven weight gradients in one grid: every operand (saved activations, the gradient buffers
+  // of the workspace, dy) is still alive here, and one launch fills the chip evenly where the
+  // separate products leave partly filled rounds (and two of them are too small to fill it at all).
+  const GemmArgs wg[7] = {
+      wgrad_args(dy, s.a, T, D, F, dw->w_down, acc),      wgrad_args(k.da_dg, s.h2, T, F, D, dw->w_gate, acc),
+      wgrad_args(k.du, s.h2, T, F, D, dw->w_up, acc),     wgrad_args(k.dy1, s.o, T, D, QD, dw->wo, acc),
+      wgrad_args(k.dq, s.h1, T, QD, D, dw->wq, acc),      wgrad_args(k.dk, s.h1, T, KD, D, dw->wk, acc),
+      wgrad_args(k.dv, s.h1, T, KD, D, dw->wv, acc)};
+  TRY(launch_gemm_group(wg, 7, st));
   return DLAYER_OK;
 }
 

@@ -181,8 +181,9 @@ struct LoadCursor {
   }
 };
 
+// One output tile of problem `p`; `pid` is the tile's position in that problem's tile sequence.
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
+__device__ __forceinline__ void gemm_tile(const GemmKArgs& p, const int pid) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int FM = TM / MI, FN = TN / MI;
@@ -202,13 +203,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wave_m = wave % WM, wave_n = wave / WM;
 
-  // Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every
-  // XCD a contiguous range of the tile sequence, and walk that sequence in bands of 8 tile-rows so
-  // that the ~32 tiles an XCD holds at a time share A and B panels.
-  int pid = blockIdx.x;
-  const int ntiles = p.tiles_m * p.tiles_n;
-  const int per_xcd = ntiles >> 3;
-  if (pid < (per_xcd << 3)) pid = (pid & 7) * per_xcd + (pid >> 3);
+  // The tile sequence runs in bands of 8 tile-rows, so that the ~32 consecutive tiles an XCD holds at
+  // a time share A and B panels.
   constexpr int GM = 8;
   const int band = pid / (GM * p.tiles_n);
   const int first_m = band * GM;
@@ -363,14 +359,78 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   }
 }
 
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous
+// range of the tile sequence.
+__device__ __forceinline__ int xcd_contiguous(int id, int ntiles) {
+  const int per_xcd = ntiles >> 3;
+  return id < (per_xcd << 3) ? (id & 7) * per_xcd + (id >> 3) : id;
+}
+
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
+  gemm_tile<BM, BN, WM, WN, AK, BKM>(p, xcd_contiguous((int)blockIdx.x, p.tiles_m * p.tiles_n));
+}
+
+// Several independent problems of one operand layout in one grid: their tile sequences are laid end
+// to end, so the last, partly filled round of one problem runs alongside the first of the next.
+constexpr int MAX_GROUP = 8;
+struct GemmGroupKArgs {
+  GemmKArgs prob[MAX_GROUP];
+  int tile_start[MAX_GROUP + 1];
+  int n;
+};
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_group_kernel(const GemmGroupKArgs g) {
+  const int pid = xcd_contiguous((int)blockIdx.x, g.tile_start[g.n]);
+  int i = 0;
+  while (i + 1 < g.n && pid >= g.tile_start[i + 1]) ++i;
+  gemm_tile<BM, BN, WM, WN, AK, BKM>(g.prob[i], pid - g.tile_start[i]);
+}
+
+template <int BM, int BN>
+static size_t lds_bytes(int nwaves, int wm) {
+  const size_t ring = (size_t)NS * (BM + BN) * BK * 2, staging = (size_t)nwaves * (BM / wm) * 128;
+  return ring > staging ? ring : staging;
+}
+
+template <int BM, int BN, int WM, int WN>
+static int launch_group_cfg(const GemmKArgs* ks, int n, bool ak, bool bk, hipStream_t st) {
+  GemmGroupKArgs g{};
+  g.n = n;
+  for (int i = 0; i < n; ++i) {
+    g.prob[i] = ks[i];
+    g.prob[i].tiles_m = (ks[i].M + BM - 1) / BM;
+    g.prob[i].tiles_n = (ks[i].N + BN - 1) / BN;
+    g.tile_start[i + 1] = g.tile_start[i] + g.prob[i].tiles_m * g.prob[i].tiles_n;
+  }
+  const dim3 grid((unsigned)g.tile_start[n]), block(WM * WN * 64);
+  const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
+#define GEMM_GROUP_LAUNCH(AK_, BK_)                                                              \
+  do {                                                                                           \
+    auto kern = gemm_group_kernel<BM, BN, WM, WN, AK_, BK_>;                                     \
+    static bool attr_set = false;                                                                \
+    if (!attr_set) {                                                                             \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                    \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+      if (e != hipSuccess) return fail(-3, "gemm: cannot reserve %zu B of LDS: %s", lds, hipGetErrorString(e)); \
+      attr_set = true;                                                                           \
+    }                                                                                            \
+    hipLaunchKernelGGL(kern, grid, block, lds, st, g);                                           \
+  } while (0)
+  // only the layout the weight-gradient products use is instantiated
+  if (!ak && !bk) GEMM_GROUP_LAUNCH(false, false);
+  else return fail(-1, "gemm group: operand layout not built");
+#undef GEMM_GROUP_LAUNCH
+  return check_launch("gemm group");
+}
+
 template <int BM, int BN, int WM, int WN>
 static int launch_cfg(const GemmKArgs& k, bool ak, bool bk, hipStream_t st) {
   GemmKArgs a = k;
   a.tiles_m = (k.M + BM - 1) / BM;
   a.tiles_n = (k.N + BN - 1) / BN;
   const dim3 grid((unsigned)(a.tiles_m * a.tiles_n)), block(WM * WN * 64);
-  const size_t ring = (size_t)NS * (BM + BN) * BK * 2, staging = (size_t)WM * WN * (BM / WM) * 128;
-  const size_t lds = ring > staging ? ring : staging;
+  const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
 #define GEMM_LAUNCH(AK_, BK_)                                                                    \
   do {                                                                                           \
     auto kern = gemm_kernel<BM, BN, WM, WN, AK_, BK_>;                                           \
@@ -391,7 +451,7 @@ static int launch_cfg(const GemmKArgs& k, bool ak, bool bk, hipStream_t st) {
   return check_launch("gemm");
 }
 
-int launch_gemm(const GemmArgs& g, hipStream_t st) {
+static GemmKArgs kernel_args(const GemmArgs& g) {
   GemmKArgs k{};
   k.nseg = g.nseg;
   for (int s = 0; s < g.nseg; ++s) {
@@ -407,11 +467,30 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   k.ldc = g.ldc;
   k.r = (const bf16_t*)g.r;
   k.accumulate = g.accumulate;
+  return k;
+}
+
+int launch_gemm(const GemmArgs& g, hipStream_t st) {
+  const GemmKArgs k = kernel_args(g);
   // Large problems: 256x256 tiles, 8 waves (2 per SIMD), 128x64 per wave.  Small ones: 128x128
   // tiles so that the grid still covers the 256 CUs.
   const int64_t tiles256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
   if (tiles256 >= 192) return launch_cfg<256, 256, 2, 4>(k, g.a_kmajor, g.b_kmajor, st);
   return launch_cfg<128, 128, 2, 2>(k, g.a_kmajor, g.b_kmajor, st);
+}
+
+int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st) {
+  if (n < 1 || n > MAX_GROUP) return fail(-1, "gemm group: 1..%d problems, got %d", MAX_GROUP, n);
+  GemmKArgs ks[MAX_GROUP];
+  int64_t tiles256 = 0;
+  for (int i = 0; i < n; ++i) {
+    if (gs[i].a_kmajor != gs[0].a_kmajor || gs[i].b_kmajor != gs[0].b_kmajor)
+      return fail(-1, "gemm group: all problems must share one operand layout");
+    ks[i] = kernel_args(gs[i]);
+    tiles256 += (int64_t)((gs[i].M + 255) / 256) * ((gs[i].N + 255) / 256);
+  }
+  if (tiles256 >= 192) return launch_group_cfg<256, 256, 2, 4>(ks, n, gs[0].a_kmajor, gs[0].b_kmajor, st);
+  return launch_group_cfg<128, 128, 2, 2>(ks, n, gs[0].a_kmajor, gs[0].b_kmajor, st);
 }
 
 }  // namespace dl

@@ -48,6 +48,9 @@ struct GemmArgs {
   bool a_kmajor, b_kmajor;
 };
 int launch_gemm(const GemmArgs& g, hipStream_t st);
+// Up to 8 independent problems with the same a_kmajor/b_kmajor in one launch (only the layout of
+// the weight-gradient product, both operands mn-major, is built).
+int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st);
 
 // ---- attention.hip
 int launch_attention_fwd(const void* q, const void* k, const void* v, int64_t B, int64_t S,
