@@ -139,8 +139,8 @@ int linear_forward(const void* x, const void* w, const void* residual, int64_t T
                    int64_t N, void* y, void* stream);
 
 /* Gradients of y = x W^T: dx = dy W ([T, K], skipped if dx == NULL) and dw = dy^T x ([N, K],
- * skipped if dw == NULL).  T, K, N multiples of 64.  workspace:
- * linear_backward_workspace_bytes(T, K, N).                                                 */
+ * skipped if dw == NULL).  T, K, N multiples of 64.  workspace (device, needed when dx is
+ * asked for: it receives a transposed copy of w): linear_backward_workspace_bytes(T, K, N).   */
 size_t linear_backward_workspace_bytes(int64_t T, int64_t K, int64_t N);
 int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int64_t K,
                     int64_t N, void* dx, void* dw, int accumulate_dw, void* workspace,

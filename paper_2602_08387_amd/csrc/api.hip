@@ -105,6 +105,7 @@ static Saved carve_saved(const dlayer_cfg* c, void* p) {
 
 struct Work {
   void *da_dg, *du, *dh2, *dy1, *d_o, *dq, *dk, *dv, *dh1, *attn_ws, *rms_ws;
+  void *wqT, *wkT, *wvT, *woT, *wgT, *wuT, *wdT;   // W^T copies: the input-gradient products then read both operands k-major
   size_t bytes;
 };
 static Work carve_work(const dlayer_cfg* c, void* p) {
@@ -123,6 +124,8 @@ static Work carve_work(const dlayer_cfg* c, void* p) {
   w.dh1 = cv.take(T * D * 2);
   w.attn_ws = cv.take(attention_bwd_workspace(c->batch, c->seq, c->n_q_heads, c->n_kv_heads, c->head_dim));
   w.rms_ws = cv.take(rmsnorm_bwd_workspace(T, D));
+  w.wqT = cv.take(QD * D * 2); w.wkT = cv.take(KD * D * 2); w.wvT = cv.take(KD * D * 2); w.woT = cv.take(D * QD * 2);
+  w.wgT = cv.take(F * D * 2); w.wuT = cv.take(F * D * 2); w.wdT = cv.take(D * F * 2);
   w.bytes = cv.off;
   return w;
 }
@@ -137,14 +140,14 @@ static int gemm_nt(const void* x, const void* w, const void* res, int64_t T, int
   g.a_kmajor = true; g.b_kmajor = true;
   return launch_gemm(g, st);
 }
-// dx[T,K] = sum_s dy_s[T,N_s] W_s[N_s,K]
-static int gemm_dgrad(int nseg, const void* const* dy, const void* const* w, const int64_t* Ns, int64_t T,
-                      int64_t K, void* dx, hipStream_t st) {
+// dx[T,K] = sum_s dy_s[T,N_s] WT_s[K,N_s]^T with the transposed weights WT_s = W_s^T
+static int gemm_dgrad_t(int nseg, const void* const* dy, const void* const* wt, const int64_t* Ns, int64_t T,
+                        int64_t K, void* dx, hipStream_t st) {
   GemmArgs g{};
   g.nseg = nseg;
-  for (int s = 0; s < nseg; ++s) g.seg[s] = {dy[s], w[s], Ns[s], K, (int)Ns[s]};
+  for (int s = 0; s < nseg; ++s) g.seg[s] = {dy[s], wt[s], Ns[s], Ns[s], (int)Ns[s]};
   g.M = (int)T; g.N = (int)K; g.c = dx; g.ldc = K; g.r = nullptr; g.accumulate = 0;
-  g.a_kmajor = true; g.b_kmajor = false;
+  g.a_kmajor = true; g.b_kmajor = true;
   return launch_gemm(g, st);
 }
 // dw[N,K] (+)= dy[T,N]^T x[T,K]
@@ -227,29 +230,36 @@ int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* 
   const int64_t Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, dh = cfg->head_dim, QD = Hq * dh, KD = Hkv * dh;
   Saved s = carve_saved(cfg, const_cast<void*>(saved));
   Work k = carve_work(cfg, workspace);
+  TRY(launch_transpose(w->w_down, k.wdT, D, F, st));
+  TRY(launch_transpose(w->w_gate, k.wgT, F, D, st));
+  TRY(launch_transpose(w->w_up, k.wuT, F, D, st));
+  TRY(launch_transpose(w->wo, k.woT, D, QD, st));
+  TRY(launch_transpose(w->wq, k.wqT, QD, D, st));
+  TRY(launch_transpose(w->wk, k.wkT, KD, D, st));
+  TRY(launch_transpose(w->wv, k.wvT, KD, D, st));
   // y = y1 + a Wd^T
   {
-    const void* dys[1] = {dy}; const void* ws[1] = {w->w_down}; const int64_t ns[1] = {D};
-    TRY(gemm_dgrad(1, dys, ws, ns, T, F, k.da_dg, st));
+    const void* dys[1] = {dy}; const void* ws[1] = {k.wdT}; const int64_t ns[1] = {D};
+    TRY(gemm_dgrad_t(1, dys, ws, ns, T, F, k.da_dg, st));
   }
   TRY(launch_swiglu_bwd(s.g, s.u, k.da_dg, T * F, k.da_dg, k.du, st));
   {
-    const void* dys[2] = {k.da_dg, k.du}; const void* ws[2] = {w->w_gate, w->w_up}; const int64_t ns[2] = {F, F};
-    TRY(gemm_dgrad(2, dys, ws, ns, T, D, k.dh2, st));
+    const void* dys[2] = {k.da_dg, k.du}; const void* ws[2] = {k.wgT, k.wuT}; const int64_t ns[2] = {F, F};
+    TRY(gemm_dgrad_t(2, dys, ws, ns, T, D, k.dh2, st));
   }
   TRY(launch_rmsnorm_bwd(s.y1, w->g_mlp, s.rstd2, k.dh2, dy, T, D, k.dy1, dw->g_mlp, acc, k.rms_ws, st));
   // y1 = x + o Wo^T
   {
-    const void* dys[1] = {k.dy1}; const void* ws[1] = {w->wo}; const int64_t ns[1] = {D};
-    TRY(gemm_dgrad(1, dys, ws, ns, T, QD, k.d_o, st));
+    const void* dys[1] = {k.dy1}; const void* ws[1] = {k.woT}; const int64_t ns[1] = {D};
+    TRY(gemm_dgrad_t(1, dys, ws, ns, T, QD, k.d_o, st));
   }
   TRY(launch_attention_bwd(s.q, s.k, s.v, s.o, k.d_o, s.lse, B, S, Hq, Hkv, dh, k.dq, k.dk, k.dv, k.attn_ws, st));
   TRY(launch_rope(k.dq, B, S, Hq, dh, cfg->rope_base, cfg->rope_layout, 1, st));
   TRY(launch_rope(k.dk, B, S, Hkv, dh, cfg->rope_base, cfg->rope_layout, 1, st));
   {
-    const void* dys[3] = {k.dq, k.dk, k.dv}; const void* ws[3] = {w->wq, w->wk, w->wv};
+    const void* dys[3] = {k.dq, k.dk, k.dv}; const void* ws[3] = {k.wqT, k.wkT, k.wvT};
     const int64_t ns[3] = {QD, KD, KD};
-    TRY(gemm_dgrad(3, dys, ws, ns, T, D, k.dh1, st));
+    TRY(gemm_dgrad_t(3, dys, ws, ns, T, D, k.dh1, st));
   }
   TRY(launch_rmsnorm_bwd(x, w->g_attn, s.rstd1, k.dh1, k.dy1, T, D, dx, dw->g_attn, acc, k.rms_ws, st));
   // All seven weight gradients in one grid: every operand (saved activations, the gradient buffers
@@ -310,11 +320,12 @@ int linear_forward(const void* x, const void* w, const void* residual, int64_t T
   return gemm_nt(x, w, residual, T, K, N, y, (hipStream_t)stream);
 }
 
-size_t linear_backward_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
+size_t linear_backward_workspace_bytes(int64_t T, int64_t K, int64_t N) {
+  return T > 0 && K > 0 && N > 0 ? (size_t)N * K * 2 : 0;   // W^T for the input-gradient product
+}
 
 int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int64_t K, int64_t N, void* dx,
                     void* dw, int accumulate_dw, void* workspace, void* stream) {
-  (void)workspace;
   REQUIRE(T > 0 && K > 0 && N > 0 && T % 64 == 0 && K % 64 == 0 && N % 64 == 0,
           "linear_backward: T, K and N must be multiples of 64");
   REQUIRE(T * K * 2 < ((int64_t)1 << 32) && N * K * 2 < ((int64_t)1 << 32) && T * N * 2 < ((int64_t)1 << 32),
@@ -324,8 +335,10 @@ int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int
   TRY(check_device());
   hipStream_t st = (hipStream_t)stream;
   if (dx) {
-    const void* dys[1] = {dy}; const void* ws[1] = {w}; const int64_t ns[1] = {N};
-    TRY(gemm_dgrad(1, dys, ws, ns, T, K, dx, st));
+    REQUIRE_PTR(workspace);
+    TRY(launch_transpose(w, workspace, N, K, st));
+    const void* dys[1] = {dy}; const void* ws[1] = {workspace}; const int64_t ns[1] = {N};
+    TRY(gemm_dgrad_t(1, dys, ws, ns, T, K, dx, st));
   }
   if (dw) TRY(gemm_wgrad(dy, x, T, N, K, dw, accumulate_dw ? 1 : 0, st));
   return DLAYER_OK;

@@ -151,10 +151,11 @@ struct LoadCursor {
   TileLoader<BN, BKM, NW> lb;
   __amdgpu_buffer_rsrc_t ra, rb;
   int64_t lda, ldb;
-  int seg = 0, k = 0;
+  int seg = 0, k = 0, kend = 0;   // kend: K of the open segment (kept in a register: no kernarg read per K-step)
 
   __device__ __forceinline__ void open(const GemmKArgs& p, int s, int m0, int n0, int lane) {
     const int K = p.K[s];
+    kend = K;
     lda = p.lda[s];
     ldb = p.ldb[s];
     const bf16_t* ab = AK ? p.a[s] + (int64_t)m0 * lda : p.a[s] + m0;
@@ -173,7 +174,7 @@ struct LoadCursor {
       la.issue(ra, stage, wave, lda, k);
       lb.issue(rb, stage + BM * BK * 2, wave, ldb, k);
       k += BK;
-      if (k == p.K[seg]) {
+      if (k == kend) {
         k = 0;
         if (++seg < p.nseg) open(p, seg, m0, n0, lane);
       }

@@ -123,7 +123,8 @@ def test_linear_backward(K, T, Kd, N):
     xd, wd, dd = map(dev_bf16, (xb, wb, db))
     dx = torch.full((T, Kd), float("nan"), dtype=torch.bfloat16, device="cuda")
     dw = torch.full((N, Kd), float("nan"), dtype=torch.bfloat16, device="cuda")
-    K.linear_backward(xd, wd, dd, T, Kd, N, dx, dw, 0, None)
+    ws = torch.empty(K.linear_backward_workspace_bytes(T, Kd, N), dtype=torch.uint8, device="cuda")
+    K.linear_backward(xd, wd, dd, T, Kd, N, dx, dw, 0, ws)
     assert_close(dx, dy @ w, "dx", rel_tol=8e-3)
     assert_close(dw, dy.T @ x, "dw", rel_tol=8e-3)
     K.linear_backward(xd, wd, dd, T, Kd, N, None, dw, 1, None)

@@ -44,7 +44,7 @@ def run_stack(K, cfg, raw, V):
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     K.ce_loss_fwd_bwd(logits, tgt, T, V, 1.0, loss, logits, _buf(K.ce_loss_workspace_bytes(T, V)))  # in place
     dh_f, dw_lm = bf(T, D), bf(V, D)
-    K.linear_backward(h_f, w_lm, logits, T, D, V, dh_f, dw_lm, 0, None)
+    K.linear_backward(h_f, w_lm, logits, T, D, V, dh_f, dw_lm, 0, _buf(K.linear_backward_workspace_bytes(T, D, V)))
     dx, dg_f = bf(T, D), bf(D)
     K.rmsnorm_backward(xs[L], g_f, rstd_f, dh_f, None, T, D, dx, dg_f, 0, _buf(K.rmsnorm_backward_workspace_bytes(T, D)))
     dW = [{n: torch.full_like(t, float("nan")) for n, t in W[l].items()} for l in range(L)]
@@ -100,7 +100,7 @@ def test_lm_head_and_loss_at_full_vocab_width(K):
     K.ce_loss_fwd_bwd(lg, td, T, V, 1.0, loss, lg, _buf(K.ce_loss_workspace_bytes(T, V)))
     assert abs(loss.item() - loss_ref) <= 1e-3 * loss_ref
     dh, dw = torch.empty_like(hd), torch.empty_like(wd)
-    K.linear_backward(hd, wd, lg, T, D, V, dh, dw, 0, None)
+    K.linear_backward(hd, wd, lg, T, D, V, dh, dw, 0, _buf(K.linear_backward_workspace_bytes(T, D, V)))
     assert_close(dh, dlg @ w, "dh_f", rel_tol=np.inf)
     rows = np.concatenate([tg[:32], rng.integers(0, V, 96)])
     assert_close(host_f64(dw)[rows], dlg[:, rows].T @ h, "dW_lm[sampled rows]", rel_tol=np.inf)
