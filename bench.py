@@ -22,6 +22,25 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/s)
 
+# HBM bytes per launch of the dominant kernel (mean over the seven forward-projection launches of the
+# 8B-shaped layer), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain 1 GiB copy in the same
+# run (factors 2.0 and 1.0; profiles/layer_8b_hbm_traffic.txt).  Only valid for the GEMM source the
+# counters were taken on: reported as null when gemm.hip has changed since.
+GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "bc5e10ccfb56b71b0d5b6c1c48691da3504a1eac585cbc83969ea62a0f6407b5",
+                "fetch_bytes": 1.508e9, "write_bytes": 0.242e9}
+
+
+def _gemm_traffic(config_name):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2602_08387_amd", "csrc", "gemm.hip")
+    try:
+        same = hashlib.sha256(open(src, "rb").read()).hexdigest() == GEMM_TRAFFIC["gemm_hip_sha256"]
+    except OSError:
+        same = False
+    if not same or config_name != GEMM_TRAFFIC["config"]:
+        return None
+    return GEMM_TRAFFIC["fetch_bytes"] + GEMM_TRAFFIC["write_bytes"]
+
 
 def _describe(cfg):
     return (f"decoder layer B{cfg.batch} S{cfg.seq} D{cfg.d_model} {cfg.n_q_heads}q/{cfg.n_kv_heads}kv x"
@@ -151,7 +170,10 @@ def main():
     achieved = gemm_flops / (total_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_kernel<256,256,2,4,k-major,k-major> (7 projection launches/step)",
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "avg_launch_ms": total_ms / len(dur_ms), "launches_timed": len(dur_ms), "traffic": None}
+                "avg_launch_ms": total_ms / len(dur_ms), "launches_timed": len(dur_ms),
+                "traffic": _gemm_traffic(args.config), "traffic_unit": "HBM bytes per launch (fetched + written)",
+                "algorithmic_bytes_per_launch": sum(2.0 * (T * Kd + N * Kd + T * N * (2 if n in ("wo", "w_down") else 1))
+                                                    for n, Kd, N in launches) / len(launches)}
 
     out = {
         "metric": "decoder-layer fwd+bwd TFLOP/s", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
