@@ -146,6 +146,16 @@ int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int
                     int64_t N, void* dx, void* dw, int accumulate_dw, void* workspace,
                     void* stream);
 
+/* Weight gradients of n (1..8) linear layers over the same T tokens in ONE launch:
+ * dw[i] [N[i], K[i]] (+)= dy[i]^T x[i] with dy[i] [T, N[i]], x[i] [T, K[i]], all bf16 row-major device
+ * pointers; dy, x, dw, N, K are host arrays of length n.  T, N[i], K[i] multiples of 64.  The tile
+ * sequences of the n products are laid end to end, so a product that leaves the last round of
+ * workgroups partly filled (or is too small to fill the chip) runs alongside the next one;
+ * dlayer_backward computes its seven weight gradients this way (Sec. 3.1's layer, backward).
+ * Results are bitwise those of n linear_backward calls with dx == NULL.                      */
+int linear_wgrad_group(int32_t n, const void* const* dy, const void* const* x, const int64_t* N,
+                       const int64_t* K, int64_t T, void* const* dw, int accumulate_dw, void* stream);
+
 /* Rotary embedding applied in place to z [B*S, H, head_dim] bf16 (see dlayer_cfg for the angle
  * and the two pairings); inverse != 0 rotates by the negative angle, which is the gradient
  * map of the forward rotation.                                                              */

@@ -2,16 +2,31 @@
 
 Every function here only marshals arguments (device pointers of torch tensors, sizes, the
 current stream) into the entry point of the same name declared in include/dlayer.h.  All
-arithmetic runs in the HIP kernels of libdlayer.so; there is no CPU or PyTorch fallback:
-importing the binding without the built library raises.
+arithmetic runs in the HIP kernels of libdlayer.so; there is no CPU or PyTorch fallback: the first
+use of any name of the binding without the built library raises.
+
+The binding is loaded on first use, not on import, so that `paper_2602_08387_amd.build` (which
+compiles the library) can be imported on a tree that holds no library yet.
 """
-from .binding import (  # noqa: F401
-    DLayerError, LayerCfg, lib, lib_path,
-    dlayer_version, dlayer_saved_bytes, dlayer_workspace_bytes, dlayer_forward, dlayer_backward,
-    ce_loss_workspace_bytes, ce_loss_fwd_bwd,
-    rmsnorm_forward, rmsnorm_backward, rmsnorm_backward_workspace_bytes,
-    linear_forward, linear_backward, linear_backward_workspace_bytes,
-    rope_apply, attention_forward, attention_backward, attention_backward_workspace_bytes,
-    swiglu_forward, swiglu_backward, embed_forward, embed_backward,
-    EXPORTED_SYMBOLS, WEIGHT_FIELDS,
+import importlib
+
+_BINDING_NAMES = (
+    "DLayerError", "LayerCfg", "lib", "lib_path",
+    "dlayer_version", "dlayer_saved_bytes", "dlayer_workspace_bytes", "dlayer_forward", "dlayer_backward",
+    "ce_loss_workspace_bytes", "ce_loss_fwd_bwd",
+    "rmsnorm_forward", "rmsnorm_backward", "rmsnorm_backward_workspace_bytes",
+    "linear_forward", "linear_backward", "linear_backward_workspace_bytes", "linear_wgrad_group",
+    "rope_apply", "attention_forward", "attention_backward", "attention_backward_workspace_bytes",
+    "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",
+    "EXPORTED_SYMBOLS", "WEIGHT_FIELDS",
 )
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES:
+        return getattr(importlib.import_module(".binding", __name__), name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")
+
+
+def __dir__():
+    return sorted(list(globals()) + list(_BINDING_NAMES))

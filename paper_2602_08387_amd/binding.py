@@ -13,7 +13,7 @@ EXPORTED_SYMBOLS = (
     "dlayer_version", "dlayer_last_error", "dlayer_saved_bytes", "dlayer_workspace_bytes",
     "dlayer_forward", "dlayer_backward", "ce_loss_workspace_bytes", "ce_loss_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward_workspace_bytes", "rmsnorm_backward",
-    "linear_forward", "linear_backward_workspace_bytes", "linear_backward", "rope_apply",
+    "linear_forward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
     "attention_forward", "attention_backward_workspace_bytes", "attention_backward",
     "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",
 )
@@ -66,6 +66,7 @@ def _load():
         "linear_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp]),
         "linear_backward_workspace_bytes": (sz, [i64, i64, i64]),
         "linear_backward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp, C.c_int, vp, vp]),
+        "linear_wgrad_group": (C.c_int, [i32, vp, vp, vp, vp, i64, vp, C.c_int, vp]),
         "rope_apply": (C.c_int, [vp, i64, i64, i64, i64, f32, i32, i32, vp]),
         "attention_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp]),
         "attention_backward_workspace_bytes": (sz, [i64, i64, i64, i64, i64]),
@@ -169,6 +170,15 @@ def linear_backward_workspace_bytes(T, K, N) -> int:
 def linear_backward(x, w, dy, T, K, N, dx, dw, accumulate_dw, workspace, stream=None):
     _check(lib.linear_backward(_p(x), _p(w), _p(dy), T, K, N, _p(dx), _p(dw), int(accumulate_dw),
                                _p(workspace), _stream(stream)), "linear_backward")
+
+
+def linear_wgrad_group(dys, xs, Ns, Ks, T, dws, accumulate_dw, stream=None):
+    n = len(dys)
+    assert len(xs) == len(Ns) == len(Ks) == len(dws) == n
+    ptrs = lambda ts: (C.c_void_p * n)(*[_p(t) for t in ts])
+    i64s = lambda vs: (C.c_int64 * n)(*[int(v) for v in vs])
+    _check(lib.linear_wgrad_group(n, ptrs(dys), ptrs(xs), i64s(Ns), i64s(Ks), T, ptrs(dws), int(accumulate_dw),
+                                  _stream(stream)), "linear_wgrad_group")
 
 
 def rope_apply(z, batch, seq, n_heads, head_dim, rope_base, rope_layout, inverse, stream=None):

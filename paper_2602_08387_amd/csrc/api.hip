@@ -344,6 +344,25 @@ int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int
   return DLAYER_OK;
 }
 
+int linear_wgrad_group(int32_t n, const void* const* dy, const void* const* x, const int64_t* N, const int64_t* K,
+                       int64_t T, void* const* dw, int accumulate_dw, void* stream) {
+  REQUIRE(n >= 1 && n <= 8, "linear_wgrad_group: 1..8 products, got %d", (int)n);
+  REQUIRE(dy && x && N && K && dw, "linear_wgrad_group: null argument array");
+  REQUIRE(T > 0 && T % 64 == 0, "linear_wgrad_group: T must be a positive multiple of 64");
+  GemmArgs gs[8];
+  for (int i = 0; i < n; ++i) {
+    REQUIRE(N[i] > 0 && K[i] > 0 && N[i] % 64 == 0 && K[i] % 64 == 0,
+            "linear_wgrad_group: N[%d] and K[%d] must be positive multiples of 64", i, i);
+    REQUIRE(T * K[i] * 2 < ((int64_t)1 << 32) && N[i] * K[i] * 2 < ((int64_t)1 << 32) && T * N[i] * 2 < ((int64_t)1 << 32),
+            "linear_wgrad_group: an operand of product %d reaches 4 GiB", i);
+    REQUIRE(dy[i] && x[i] && dw[i] && aligned16(dy[i]) && aligned16(x[i]) && aligned16(dw[i]),
+            "linear_wgrad_group: a pointer of product %d is null or not 16-byte aligned", i);
+    gs[i] = wgrad_args(dy[i], x[i], T, N[i], K[i], dw[i], accumulate_dw ? 1 : 0);
+  }
+  TRY(check_device());
+  return launch_gemm_group(gs, n, (hipStream_t)stream);
+}
+
 int rope_apply(void* z, int64_t batch, int64_t seq, int64_t n_heads, int64_t head_dim, float rope_base,
                int32_t rope_layout, int32_t inverse, void* stream) {
   REQUIRE(batch > 0 && seq > 0 && n_heads > 0, "rope_apply: non-positive dimension");

@@ -131,6 +131,72 @@ def test_linear_backward(K, T, Kd, N):
     assert_close(dw, 2 * (dy.T @ x), "dw accumulated", rel_tol=1.2e-2)
 
 
+def test_linear_wgrad_group(K):
+    """Several weight-gradient products in one launch: against the oracle, and bitwise against the
+    same products launched one by one."""
+    rng = np.random.default_rng(11)
+    T, shapes = 1024, [(320, 256), (64, 64), (1536, 512), (128, 1024)]   # (N, K) per product
+    dyb = [_rand_bits(rng, (T, N)) for N, _ in shapes]
+    xb = [_rand_bits(rng, (T, Kd)) for _, Kd in shapes]
+    dyd, xd = [dev_bf16(b) for b in dyb], [dev_bf16(b) for b in xb]
+    dws = [torch.full((N, Kd), float("nan"), dtype=torch.bfloat16, device="cuda") for N, Kd in shapes]
+    K.linear_wgrad_group(dyd, xd, [N for N, _ in shapes], [Kd for _, Kd in shapes], T, dws, 0)
+    for i, (N, Kd) in enumerate(shapes):
+        ref = si.bf16_bits_to_f64(dyb[i]).T @ si.bf16_bits_to_f64(xb[i])
+        assert_close(dws[i], ref, f"dw[{i}]", rel_tol=8e-3)
+        one = torch.empty_like(dws[i])
+        K.linear_backward(xd[i], xd[i], dyd[i], T, Kd, N, None, one, 0, None)
+        assert torch.equal(one.view(torch.int16), dws[i].view(torch.int16)), f"grouped dw[{i}] differs from the single launch"
+    K.linear_wgrad_group(dyd, xd, [N for N, _ in shapes], [Kd for _, Kd in shapes], T, dws, 1)
+    for i in range(len(shapes)):
+        ref = si.bf16_bits_to_f64(dyb[i]).T @ si.bf16_bits_to_f64(xb[i])
+        assert_close(dws[i], 2 * ref, f"dw[{i}] accumulated", rel_tol=1.2e-2)
+    with pytest.raises(K.DLayerError, match="multiples of 64"):
+        K.linear_wgrad_group(dyd[:1], xd[:1], [100], [256], T, dws[:1], 0)
+
+
+@pytest.mark.parametrize("Kd,N,res", [(4096, 14336, False), (14336, 4096, True)])
+def test_linear_full_size_sampled(K, Kd, N, res):
+    """The two widest projections of the 8B-shaped layer at their full size (T = 16384), as the
+    benchmark launches them.  The oracle computes sampled outputs one by one (fp64 dot products over
+    the bf16 operands); a row-sum identity covers every output tile."""
+    T = 16384
+    rng = np.random.default_rng(Kd)
+    xb, wb = _rand_bits(rng, (T, Kd)), _rand_bits(rng, (N, Kd), 0.02)
+    rb, db = _rand_bits(rng, (T, N)), _rand_bits(rng, (T, N))
+    xd, wd, rd, dd = map(dev_bf16, (xb, wb, rb, db))
+    y = torch.full((T, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    K.linear_forward(xd, wd, rd if res else None, T, Kd, N, y)
+    ns = 4096
+    m = np.concatenate([rng.integers(0, T, ns - 8), [0, T - 1, 255, 256, T - 257, T - 256, 8191, 8192]])
+    n = np.concatenate([rng.integers(0, N, ns - 8), [0, N - 1, N - 1, 0, 255, 256, N - 256, N - 257]])
+    x, w = si.bf16_bits_to_f64(xb), si.bf16_bits_to_f64(wb)
+    ref = np.einsum("ik,ik->i", x[m], w[n]) + (si.bf16_bits_to_f64(rb[m, n]) if res else 0.0)
+    got = host_f64(y[torch.from_numpy(m).cuda(), torch.from_numpy(n).cuda()])
+    assert_close(got, ref, "y[sampled]", rel_tol=8e-3)
+    # sum_n y[m, n] = x[m] . (sum_n W[n]) (+ sum_n r[m, n]) for every row m: each output is rounded to bf16
+    # (relative 2^-9, independent), so the row sums agree to a few 1e-3 of their rms
+    rows = x @ w.sum(axis=0) + (si.bf16_bits_to_f64(rb).sum(axis=1) if res else 0.0)
+    assert not torch.isnan(y.float()).any()
+    assert_close(y.double().sum(dim=1).cpu().numpy(), rows, "row sums of y", rel_tol=8e-3)
+    cols = w @ x.sum(axis=0) + (si.bf16_bits_to_f64(rb).sum(axis=0) if res else 0.0)
+    assert_close(y.double().sum(dim=0).cpu().numpy(), cols, "column sums of y", rel_tol=8e-3)
+    # backward at the same size
+    dx = torch.full((T, Kd), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dw = torch.full((N, Kd), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(K.linear_backward_workspace_bytes(T, Kd, N), dtype=torch.uint8, device="cuda")
+    K.linear_backward(xd, wd, dd, T, Kd, N, dx, dw, 0, ws)
+    dy = si.bf16_bits_to_f64(db)
+    mk = np.concatenate([rng.integers(0, Kd, ns - 4), [0, Kd - 1, 255, Kd - 256]])
+    ref = np.einsum("in,ni->i", dy[m], w[:, mk])
+    assert_close(host_f64(dx[torch.from_numpy(m).cuda(), torch.from_numpy(mk).cuda()]), ref, "dx[sampled]", rel_tol=8e-3)
+    assert_close(dx.double().sum(dim=1).cpu().numpy(), dy @ w.sum(axis=1), "row sums of dx", rel_tol=8e-3)
+    ref = np.einsum("ti,ti->i", dy[:, n], x[:, mk])
+    assert_close(host_f64(dw[torch.from_numpy(n).cuda(), torch.from_numpy(mk).cuda()]), ref, "dw[sampled]", rel_tol=8e-3)
+    assert_close(dw.double().sum(dim=1).cpu().numpy(), dy.T @ x.sum(axis=1), "row sums of dw", rel_tol=8e-3)
+    assert not torch.isnan(dx.float()).any() and not torch.isnan(dw.float()).any()
+
+
 # ------------------------------------------------------------------ attention
 # batch * kv heads a multiple of 8 takes the XCD-aware work placement (one or two pairs per XCD), the
 # other cases the plain one
