@@ -151,40 +151,67 @@ struct LoadCursor {
   TileLoader<BN, BKM, NW> lb;
   __amdgpu_buffer_rsrc_t ra, rb;
   int64_t lda, ldb;
-  int seg = 0, k = 0, kend = 0;   // kend: K of the open segment (kept in a register: no kernarg read per K-step)
+  int seg = 0, k = 0, kend = 0, nseg = 1;   // kend: K of the open segment (kept in a register: no kernarg read per K-step)
 
-  __device__ __forceinline__ void open(const GemmKArgs& p, int s, int m0, int n0, int lane) {
-    const int K = p.K[s];
+  __device__ __forceinline__ void open_raw(const bf16_t* a, const bf16_t* b, int64_t lda_, int64_t ldb_, int K, int M,
+                                           int N, int m0, int n0, int lane) {
     kend = K;
-    lda = p.lda[s];
-    ldb = p.ldb[s];
-    const bf16_t* ab = AK ? p.a[s] + (int64_t)m0 * lda : p.a[s] + m0;
-    const bf16_t* bb = BKM ? p.b[s] + (int64_t)n0 * ldb : p.b[s] + n0;
-    const uint32_t a_bytes = AK ? (uint32_t)((((int64_t)(p.M - m0 - 1)) * lda + K) * 2)
-                                : (uint32_t)((((int64_t)(K - 1)) * lda + (p.M - m0)) * 2);
-    const uint32_t b_bytes = BKM ? (uint32_t)((((int64_t)(p.N - n0 - 1)) * ldb + K) * 2)
-                                 : (uint32_t)((((int64_t)(K - 1)) * ldb + (p.N - n0)) * 2);
+    lda = lda_;
+    ldb = ldb_;
+    const bf16_t* ab = AK ? a + (int64_t)m0 * lda : a + m0;
+    const bf16_t* bb = BKM ? b + (int64_t)n0 * ldb : b + n0;
+    const uint32_t a_bytes = AK ? (uint32_t)((((int64_t)(M - m0 - 1)) * lda + K) * 2)
+                                : (uint32_t)((((int64_t)(K - 1)) * lda + (M - m0)) * 2);
+    const uint32_t b_bytes = BKM ? (uint32_t)((((int64_t)(N - n0 - 1)) * ldb + K) * 2)
+                                 : (uint32_t)((((int64_t)(K - 1)) * ldb + (N - n0)) * 2);
     ra = make_rsrc(ab, a_bytes);
     rb = make_rsrc(bb, b_bytes);
     la.init(lane, lda);
     lb.init(lane, ldb);
   }
-  __device__ __forceinline__ void issue_next(const GemmKArgs& p, char* stage, int wave, int m0, int n0, int lane) {
-    if (seg < p.nseg) {
+  __device__ __forceinline__ void open(const GemmKArgs& p, int s, int m0, int n0, int lane) {
+    open_raw(p.a[s], p.b[s], p.lda[s], p.ldb[s], p.K[s], p.M, p.N, m0, n0, lane);
+  }
+  // `segs`: the problem whose further K-segments follow (only read when nseg > 1)
+  __device__ __forceinline__ void issue_next(const GemmKArgs& segs, char* stage, int wave, int m0, int n0, int lane) {
+    if (seg < nseg) {
       la.issue(ra, stage, wave, lda, k);
       lb.issue(rb, stage + BM * BK * 2, wave, ldb, k);
       k += BK;
       if (k == kend) {
         k = 0;
-        if (++seg < p.nseg) open(p, seg, m0, n0, lane);
+        if (++seg < nseg) open(segs, seg, m0, n0, lane);
       }
     }
   }
 };
 
-// One output tile of problem `p`; `pid` is the tile's position in that problem's tile sequence.
-template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
-__device__ __forceinline__ void gemm_tile(const GemmKArgs& p, const int pid) {
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous
+// range of the tile sequence.
+__device__ __forceinline__ int xcd_contiguous(int id, int ntiles) {
+  const int per_xcd = ntiles >> 3;
+  return id < (per_xcd << 3) ? (id & 7) * per_xcd + (id >> 3) : id;
+}
+
+// Several independent problems of one operand layout in one grid: their tile sequences are laid end
+// to end, so the last, partly filled round of one problem runs alongside the first of the next.
+constexpr int MAX_GROUP = 8;
+struct GemmGroupKArgs {
+  GemmKArgs prob[MAX_GROUP];
+  int tile_start[MAX_GROUP + 1];
+  int n;
+};
+
+// Persistent workgroup: one per CU, walking the tile sequence with stride gridDim.x.  Between two
+// tiles the first two K-steps of the next tile are already on their way into the LDS ring while the
+// epilogue of the current one drains the accumulators through a staging region of its own, and the
+// C stores of a tile complete under the next tile's main loop.
+//
+// The kernel arguments are only ever read with compile-time offsets (a grouped launch picks its
+// problem by comparing against each index in turn): a run-time index into the argument block would
+// make the compiler copy the whole block to scratch memory and read it back through vector loads.
+template <bool GROUPED, int BM, int BN, int WM, int WN, bool AK, bool BKM>
+__device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const GemmKArgs& one) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int FM = TM / MI, FN = TN / MI;
@@ -197,201 +224,268 @@ __device__ __forceinline__ void gemm_tile(const GemmKArgs& p, const int pid) {
   using LoadA = TileLoader<BM, AK, NL>;
   using LoadB = TileLoader<BN, BKM, NL>;
   constexpr int LPW = LoadA::PER_WAVE + LoadB::PER_WAVE;   // loads per wave per stage
-  static_assert((NS - 2) * LPW <= 63, "vmcnt range");
+  static_assert(NS == 2, "the stage hand-over below is written for a two-stage ring");
+  static_assert(TN % 64 == 0 && FM % 4 == 0, "staging layout: 128-byte rows, four row quarters");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wave_m = wave % WM, wave_n = wave / WM;
-
-  // The tile sequence runs in bands of 8 tile-rows, so that the ~32 consecutive tiles an XCD holds at
-  // a time share A and B panels.
-  constexpr int GM = 8;
-  const int band = pid / (GM * p.tiles_n);
-  const int first_m = band * GM;
-  const int band_h = min(p.tiles_m - first_m, GM);
-  const int in_band = pid - band * GM * p.tiles_n;
-  const int tile_m = first_m + in_band % band_h;
-  const int tile_n = in_band / band_h;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  acc_t acc[FN][FM];
+  const bool loader = wave < NL;
+  int ntiles;
+  if constexpr (GROUPED) {
+    ntiles = grp.tile_start[1];
 #pragma unroll
-  for (int i = 0; i < FN; ++i)
-#pragma unroll
-    for (int j = 0; j < FM; ++j)
-#pragma unroll
-      for (int e = 0; e < NACC; ++e) acc[i][j][e] = 0.f;
+    for (int i = 2; i <= MAX_GROUP; ++i) if (i <= grp.n) ntiles = grp.tile_start[i];
+  } else {
+    ntiles = one.tiles_m * one.tiles_n;
+  }
 
-  int total = 0;
-  for (int s = 0; s < p.nseg; ++s) total += p.K[s] / BK;
+  // What the epilogue needs of a tile's problem, by value (the next tile's cursor is opened before the
+  // current tile's epilogue runs).
+  struct Tile { int m0, n0, total, M, N, accumulate; bf16_t* c; const bf16_t* r; int64_t ldc; };
+  LoadCursor<BM, BN, NL, AK, BKM> cur;
+
+  // tile id -> tile origin, and the load cursor opened on the tile's first K-segment.  The tile
+  // sequence of a problem runs in bands of 8 tile-rows, so that the ~32 consecutive tiles an XCD holds
+  // at a time share A and B panels.
+  auto locate = [&](int id) {
+    int pid = xcd_contiguous(id, ntiles);
+    int tiles_m, tiles_n, K0, start = 0;
+    const bf16_t *a0, *b0;
+    int64_t lda0, ldb0;
+    Tile t;
+    auto take = [&](const GemmKArgs& q) {
+      tiles_m = q.tiles_m; tiles_n = q.tiles_n; K0 = q.K[0];
+      a0 = q.a[0]; b0 = q.b[0]; lda0 = q.lda[0]; ldb0 = q.ldb[0];
+      t.M = q.M; t.N = q.N; t.accumulate = q.accumulate; t.c = q.c; t.r = q.r; t.ldc = q.ldc;
+    };
+    if constexpr (GROUPED) {
+      // problem index: the number of problems whose first tile is not after pid
+      take(grp.prob[0]);
+#pragma unroll
+      for (int i = 1; i < MAX_GROUP; ++i)
+        if (i < grp.n && pid >= grp.tile_start[i]) { take(grp.prob[i]); start = grp.tile_start[i]; }
+      pid -= start;
+      cur.nseg = 1;   // grouped problems have a single K-segment (checked on the host)
+      t.total = K0 / BK;
+    } else {
+      take(one);
+      cur.nseg = one.nseg;
+      t.total = 0;
+      for (int s2 = 0; s2 < one.nseg; ++s2) t.total += one.K[s2] / BK;
+    }
+    constexpr int GM = 8;
+    const int band = pid / (GM * tiles_n);
+    const int first_m = band * GM;
+    const int band_h = min(tiles_m - first_m, GM);
+    const int in_band = pid - band * GM * tiles_n;
+    t.m0 = (first_m + in_band % band_h) * BM;
+    t.n0 = (in_band / band_h) * BN;
+    cur.seg = 0;
+    cur.k = 0;
+    cur.open_raw(a0, b0, lda0, ldb0, K0, t.M, t.N, t.m0, t.n0, lane);
+    return t;
+  };
 
   // Load cursor: runs two K-steps ahead of the compute cursor, across segment boundaries.
-  LoadCursor<BM, BN, NL, AK, BKM> cur;
-  const bool loader = wave < NL;
-  cur.open(p, 0, m0, n0, lane);
+  int id = blockIdx.x;
+  if (id >= ntiles) return;
+  Tile tl = locate(id);
   if (loader) {
-    cur.issue_next(p, smem, wave, m0, n0, lane);
-    cur.issue_next(p, smem + STAGE, wave, m0, n0, lane);
+    cur.issue_next(one, smem, wave, tl.m0, tl.n0, lane);
+    cur.issue_next(one, smem + STAGE, wave, tl.m0, tl.n0, lane);
   }
-  if (total >= 2) wait_vmcnt<LPW>(); else wait_vmcnt<0>();
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
+  if (tl.total >= 2) wait_vmcnt<LPW>(); else wait_vmcnt<0>();
 
-  // Software-pipelined K loop: operand fragments are double-buffered in registers; the barrier that
-  // hands over to the next stage sits before the last MFMA group of the current one, so the matrix
-  // pipe stays busy while the first fragments of the next stage are fetched from LDS.
-  constexpr int KK = BK / KSTEP;
-  static_assert(NS == 2, "the hand-over below is written for a two-stage ring");
-  bf16x8 fa[2][FM], fb[2][FN];
-  {
-    const char* ta = smem;
-    const char* tb = ta + A_BYTES;
+  while (true) {
+    const Tile p = tl;   // this tile; `tl` moves on to the next one before the epilogue
+    const int m0 = tl.m0, n0 = tl.n0, total = tl.total;
+    acc_t acc[FN][FM];
 #pragma unroll
-    for (int j = 0; j < FM; ++j) fa[0][j] = read_frag<BM, AK>(ta, wave_m * TM + j * MI, 0, lane);
-#pragma unroll
-    for (int i = 0; i < FN; ++i) fb[0][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, 0, lane);
-  }
-  for (int t = 0; t < total; ++t) {
-    const char* ta = smem + (t % NS) * STAGE;
-    const char* tb = ta + A_BYTES;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const int cb = kk & 1, nb = cb ^ 1;
-      if (kk + 1 < KK) {
-#pragma unroll
-        for (int j = 0; j < FM; ++j) fa[nb][j] = read_frag<BM, AK>(ta, wave_m * TM + j * MI, kk + 1, lane);
-#pragma unroll
-        for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, kk + 1, lane);
-      } else {
-        // all of this wave's reads of stage t are in registers; stage t+1 must have landed
-        wait_vmcnt<0>();   // the only loads in flight are those of stage t+1, issued one K-step ago
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        // every wave now holds its last fragments of stage t in registers: refill that stage with
-        // step t+2 right away, so the loads get a whole K-step to land (measured global -> LDS
-        // latency under load: about 1800 cycles against a K-step of about 3000)
-        if (loader) cur.issue_next(p, smem + (t % NS) * STAGE, wave, m0, n0, lane);
-        if (t + 1 < total) {
-          const char* na = smem + ((t + 1) % NS) * STAGE;
-          const char* nbp = na + A_BYTES;
-#pragma unroll
-          for (int j = 0; j < FM; ++j) fa[nb][j] = read_frag<BM, AK>(na, wave_m * TM + j * MI, 0, lane);
-#pragma unroll
-          for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(nbp, wave_n * TN + i * MI, 0, lane);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < FN; ++i)
-#pragma unroll
-        for (int j = 0; j < FM; ++j)
-          acc[i][j] = mfma(fb[cb][i], fa[cb][j], acc[i][j]);
-#pragma unroll
-      for (int q = 0; q < FM + FN; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN) / (FM + FN), 0);  // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, AK && BKM ? 1 : 2, 0);      // DS read
-      }
-    }
-  }
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-
-  // Epilogue through LDS: each wave owns a [TM][64] bf16 staging area per 64 columns of its tile
-  // (128 bytes per row, chunk c of row m stored at c ^ ((m >> 1) & 7)), filled from the accumulator
-  // layout (8 bytes per lane) and drained row-contiguously (16 bytes per lane, 8 lanes per row).
-  static_assert(TN % 64 == 0, "staging layout assumes 128-byte rows");
-  char* stg = smem + wave * (TM * 128);
-  const int lm = lane & (MI - 1), lq = lane / MI;
-  const int rrow = lane >> 3, rpc = lane & 7;
-  constexpr int TPB = 64 / MI;      // MFMA blocks per 64 staged columns
-  constexpr int NG = NACC / 4;      // 4-column groups a lane holds per MFMA block
-  // column (within the 64 staged ones) of group g of block i for this lane
-  auto stg_off = [&](int j, int i, int g) {
-    const int row = j * MI + lm;
-    const int n = i * MI + (MI == 32 ? g * 8 + lq * 4 : lq * 4);
-    return row * 128 + ((((n >> 3) ^ ((row >> 1) & 7)) << 4) | ((n & 4) << 1));
-  };
-#pragma unroll
-  for (int nb = 0; nb < TN / 64; ++nb) {
-    const int nbase = n0 + wave_n * TN + nb * 64;
-    if (p.r || p.accumulate) {
-      const bf16_t* src = p.r ? p.r : p.c;
-#pragma unroll
-      for (int t = 0; t < TM / 8; ++t) {
-        const int row = t * 8 + rrow;
-        const int m = m0 + wave_m * TM + row;
-        const int n = nbase + ((rpc ^ ((row >> 1) & 7)) << 3);
-        bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (m < p.M && n < p.N) v = *reinterpret_cast<const bf16x8*>(src + (int64_t)m * p.ldc + n);
-        *reinterpret_cast<bf16x8*>(stg + row * 128 + (rpc << 4)) = v;
-      }
+    for (int i = 0; i < FN; ++i)
 #pragma unroll
       for (int j = 0; j < FM; ++j)
 #pragma unroll
-        for (int i = 0; i < TPB; ++i)
+        for (int e = 0; e < NACC; ++e) acc[i][j][e] = 0.f;
+
+    // K-step 0 has landed in every loading wave's share (waited for before the first tile, or in the
+    // previous tile's epilogue); the barrier makes it visible to all waves
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    // Software-pipelined K loop: operand fragments are double-buffered in registers; the barrier that
+    // hands over to the next stage sits before the last MFMA group of the current one, so the matrix
+    // pipe stays busy while the first fragments of the next stage are fetched from LDS.
+    constexpr int KK = BK / KSTEP;
+    bf16x8 fa[2][FM], fb[2][FN];
+    {
+      const char* ta = smem;
+      const char* tb = ta + A_BYTES;
 #pragma unroll
-          for (int g = 0; g < NG; ++g) {
-            const bf16x4 v = *reinterpret_cast<const bf16x4*>(stg + stg_off(j, i, g));
+      for (int j = 0; j < FM; ++j) fa[0][j] = read_frag<BM, AK>(ta, wave_m * TM + j * MI, 0, lane);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[nb * TPB + i][j][g * 4 + e] += (float)v[e];
-          }
+      for (int i = 0; i < FN; ++i) fb[0][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, 0, lane);
     }
+    for (int t = 0; t < total; ++t) {
+      char* st_cur = smem + (t & 1) * STAGE;
+      const char* ta = st_cur;
+      const char* tb = ta + A_BYTES;
 #pragma unroll
-    for (int j = 0; j < FM; ++j)
+      for (int kk = 0; kk < KK; ++kk) {
+        const int cb = kk & 1, nb = cb ^ 1;
+        if (kk + 1 < KK) {
 #pragma unroll
-      for (int i = 0; i < TPB; ++i)
+          for (int j = 0; j < FM; ++j) fa[nb][j] = read_frag<BM, AK>(ta, wave_m * TM + j * MI, kk + 1, lane);
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-          bf16x4 o;
+          for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, kk + 1, lane);
+        } else {
+          // all of this wave's reads of stage t are in registers; stage t+1 must have landed
+          wait_vmcnt<0>();   // the only loads in flight are those of stage t+1, issued one K-step ago
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+          // every wave now holds its last fragments of stage t in registers: refill that stage with
+          // step t+2 right away, so the loads get a whole K-step to land (measured global -> LDS
+          // latency under load: about 1800 cycles against a K-step of about 3000)
+          if (loader) cur.issue_next(one, st_cur, wave, m0, n0, lane);
+          if (t + 1 < total) {
+            const char* na = smem + ((t + 1) & 1) * STAGE;
+            const char* nbp = na + A_BYTES;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[nb * TPB + i][j][g * 4 + e];
-          *reinterpret_cast<bf16x4*>(stg + stg_off(j, i, g)) = o;
+            for (int j = 0; j < FM; ++j) fa[nb][j] = read_frag<BM, AK>(na, wave_m * TM + j * MI, 0, lane);
+#pragma unroll
+            for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(nbp, wave_n * TN + i * MI, 0, lane);
+          }
         }
 #pragma unroll
-    for (int t = 0; t < TM / 8; ++t) {
-      const int row = t * 8 + rrow;
-      const int m = m0 + wave_m * TM + row;
-      const int n = nbase + ((rpc ^ ((row >> 1) & 7)) << 3);
-      const bf16x8 v = *reinterpret_cast<const bf16x8*>(stg + row * 128 + (rpc << 4));
-      if (m < p.M && n < p.N) *reinterpret_cast<bf16x8*>(p.c + (int64_t)m * p.ldc + n) = v;
+        for (int i = 0; i < FN; ++i)
+#pragma unroll
+          for (int j = 0; j < FM; ++j)
+            acc[i][j] = mfma(fb[cb][i], fa[cb][j], acc[i][j]);
+#pragma unroll
+        for (int q = 0; q < FM + FN; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN) / (FM + FN), 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, AK && BKM ? 1 : 2, 0);      // DS read
+        }
+      }
     }
-  }
-}
+    // (the hand-over of the last K-step waited for every load and passed a barrier after every wave's
+    // last LDS read: the whole ring is free here)
 
-// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous
-// range of the tile sequence.
-__device__ __forceinline__ int xcd_contiguous(int id, int ntiles) {
-  const int per_xcd = ntiles >> 3;
-  return id < (per_xcd << 3) ? (id & 7) * per_xcd + (id >> 3) : id;
+    // Next tile: open its cursor and send its first two K-steps into the ring before the epilogue
+    // starts.
+    id += gridDim.x;
+    const bool more = id < ntiles;
+    if (more) {
+      tl = locate(id);
+      if (loader) {
+        cur.issue_next(one, smem, wave, tl.m0, tl.n0, lane);
+        cur.issue_next(one, smem + STAGE, wave, tl.m0, tl.n0, lane);
+      }
+    }
+
+    // Epilogue through LDS (a region behind the ring): each wave owns a [TM/4][64] bf16 staging area
+    // (128 bytes per row, chunk c of row m stored at c ^ ((m >> 1) & 7)), filled from the accumulator
+    // layout (8 bytes per lane) and drained row-contiguously (16 bytes per lane, 8 lanes per row); a
+    // wave's tile goes through it in 4 * TN/64 pieces.
+    constexpr int HM = TM / 4, HF = FM / 4;
+    char* stg = smem + NS * STAGE + wave * (HM * 128);
+    const int lm = lane & (MI - 1), lq = lane / MI;
+    const int rrow = lane >> 3, rpc = lane & 7;
+    constexpr int TPB = 64 / MI;      // MFMA blocks per 64 staged columns
+    constexpr int NG = NACC / 4;      // 4-column groups a lane holds per MFMA block
+    // column (within the 64 staged ones) of group g of block i for this lane; jj: block row in the half
+    auto stg_off = [&](int jj, int i, int g) {
+      const int row = jj * MI + lm;
+      const int n = i * MI + (MI == 32 ? g * 8 + lq * 4 : lq * 4);
+      return row * 128 + ((((n >> 3) ^ ((row >> 1) & 7)) << 4) | ((n & 4) << 1));
+    };
+#pragma unroll
+    for (int nb = 0; nb < TN / 64; ++nb) {
+      const int nbase = n0 + wave_n * TN + nb * 64;
+#pragma unroll
+      for (int hf = 0; hf < 4; ++hf) {
+        const int mbase = m0 + wave_m * TM + hf * HM;
+        if (p.r || p.accumulate) {
+          const bf16_t* src = p.r ? p.r : p.c;
+#pragma unroll
+          for (int t = 0; t < HM / 8; ++t) {
+            const int row = t * 8 + rrow;
+            const int m = mbase + row;
+            const int n = nbase + ((rpc ^ ((row >> 1) & 7)) << 3);
+            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (m < p.M && n < p.N) v = *reinterpret_cast<const bf16x8*>(src + (int64_t)m * p.ldc + n);
+            *reinterpret_cast<bf16x8*>(stg + row * 128 + (rpc << 4)) = v;
+          }
+#pragma unroll
+          for (int jj = 0; jj < HF; ++jj)
+#pragma unroll
+            for (int i = 0; i < TPB; ++i)
+#pragma unroll
+              for (int g = 0; g < NG; ++g) {
+                const bf16x4 v = *reinterpret_cast<const bf16x4*>(stg + stg_off(jj, i, g));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[nb * TPB + i][hf * HF + jj][g * 4 + e] += (float)v[e];
+              }
+        }
+#pragma unroll
+        for (int jj = 0; jj < HF; ++jj)
+#pragma unroll
+          for (int i = 0; i < TPB; ++i)
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+              bf16x4 o;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[nb * TPB + i][hf * HF + jj][g * 4 + e];
+              *reinterpret_cast<bf16x4*>(stg + stg_off(jj, i, g)) = o;
+            }
+        // Before this tile's first store: the next tile's K-step 0 must have landed, and waiting for
+        // it here (nothing younger than K-step 1 is in flight) keeps the stores out of that wait, so
+        // they complete under the next main loop.
+        if (nb == 0 && hf == 0 && more) {
+          if (tl.total >= 2) wait_vmcnt<LPW>(); else wait_vmcnt<0>();
+        }
+#pragma unroll
+        for (int t = 0; t < HM / 8; ++t) {
+          const int row = t * 8 + rrow;
+          const int m = mbase + row;
+          const int n = nbase + ((rpc ^ ((row >> 1) & 7)) << 3);
+          const bf16x8 v = *reinterpret_cast<const bf16x8*>(stg + row * 128 + (rpc << 4));
+          if (m < p.M && n < p.N) *reinterpret_cast<bf16x8*>(p.c + (int64_t)m * p.ldc + n) = v;
+        }
+      }
+    }
+    if (!more) break;
+  }
 }
 
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
-  gemm_tile<BM, BN, WM, WN, AK, BKM>(p, xcd_contiguous((int)blockIdx.x, p.tiles_m * p.tiles_n));
+  gemm_persistent<false, BM, BN, WM, WN, AK, BKM>(GemmGroupKArgs{}, p);
 }
 
-// Several independent problems of one operand layout in one grid: their tile sequences are laid end
-// to end, so the last, partly filled round of one problem runs alongside the first of the next.
-constexpr int MAX_GROUP = 8;
-struct GemmGroupKArgs {
-  GemmKArgs prob[MAX_GROUP];
-  int tile_start[MAX_GROUP + 1];
-  int n;
-};
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_group_kernel(const GemmGroupKArgs g) {
-  const int pid = xcd_contiguous((int)blockIdx.x, g.tile_start[g.n]);
-  int i = 0;
-  while (i + 1 < g.n && pid >= g.tile_start[i + 1]) ++i;
-  gemm_tile<BM, BN, WM, WN, AK, BKM>(g.prob[i], pid - g.tile_start[i]);
+  gemm_persistent<true, BM, BN, WM, WN, AK, BKM>(g, g.prob[0]);
+}
+
+// One workgroup per CU (the LDS ring allows no second one), fewer if there are fewer tiles.
+static int persistent_grid(int ntiles) {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return ntiles;
+    cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  return ntiles < cus ? ntiles : cus;
 }
 
 template <int BM, int BN>
 static size_t lds_bytes(int nwaves, int wm) {
-  const size_t ring = (size_t)NS * (BM + BN) * BK * 2, staging = (size_t)nwaves * (BM / wm) * 128;
-  return ring > staging ? ring : staging;
+  const size_t ring = (size_t)NS * (BM + BN) * BK * 2, staging = (size_t)nwaves * (BM / wm / 4) * 128;
+  return ring + staging;
 }
 
 template <int BM, int BN, int WM, int WN>
@@ -404,7 +498,7 @@ static int launch_group_cfg(const GemmKArgs* ks, int n, bool ak, bool bk, hipStr
     g.prob[i].tiles_n = (ks[i].N + BN - 1) / BN;
     g.tile_start[i + 1] = g.tile_start[i] + g.prob[i].tiles_m * g.prob[i].tiles_n;
   }
-  const dim3 grid((unsigned)g.tile_start[n]), block(WM * WN * 64);
+  const dim3 grid((unsigned)persistent_grid(g.tile_start[n])), block(WM * WN * 64);
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
 #define GEMM_GROUP_LAUNCH(AK_, BK_)                                                              \
   do {                                                                                           \
@@ -430,7 +524,7 @@ static int launch_cfg(const GemmKArgs& k, bool ak, bool bk, hipStream_t st) {
   GemmKArgs a = k;
   a.tiles_m = (k.M + BM - 1) / BM;
   a.tiles_n = (k.N + BN - 1) / BN;
-  const dim3 grid((unsigned)(a.tiles_m * a.tiles_n)), block(WM * WN * 64);
+  const dim3 grid((unsigned)persistent_grid(a.tiles_m * a.tiles_n)), block(WM * WN * 64);
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
 #define GEMM_LAUNCH(AK_, BK_)                                                                    \
   do {                                                                                           \
@@ -487,6 +581,7 @@ int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st) {
   for (int i = 0; i < n; ++i) {
     if (gs[i].a_kmajor != gs[0].a_kmajor || gs[i].b_kmajor != gs[0].b_kmajor)
       return fail(-1, "gemm group: all problems must share one operand layout");
+    if (gs[i].nseg != 1) return fail(-1, "gemm group: problems must have a single K-segment");
     ks[i] = kernel_args(gs[i]);
     tiles256 += (int64_t)((gs[i].M + 255) / 256) * ((gs[i].N + 255) / 256);
   }
