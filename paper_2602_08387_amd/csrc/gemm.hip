@@ -349,7 +349,10 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
           // step t+2 right away, so the loads get a whole K-step to land (measured global -> LDS
           // latency under load: about 1800 cycles against a K-step of about 3000)
           if (loader) cur.issue_next(one, st_cur, wave, m0, n0, lane);
-          if (t + 1 < total) {
+          // k-major x k-major: the reads go out unconditionally (after the last K-step they fetch stale
+          // bytes nobody uses), which keeps them in one block with this group's MFMAs so that the
+          // scheduler interleaves them (+2 %); with transposed reads the burst is faster (measured)
+          if ((AK && BKM) || t + 1 < total) {
             const char* na = smem + ((t + 1) & 1) * STAGE;
             const char* nbp = na + A_BYTES;
 #pragma unroll
