@@ -308,6 +308,51 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16x8* g, const 
   }
 }
 
+// Row variants: g, u are [rows, cols] with leading dimension ld_gu, the other arrays with ld_p
+// (the layer keeps a, da/dg and du with padded rows).  One row per workgroup at a time.
+__global__ __launch_bounds__(256) void swiglu_fwd_rows_kernel(const bf16_t* __restrict__ g, const bf16_t* __restrict__ u,
+                                                              bf16_t* __restrict__ a, int rows, int cols_vec,
+                                                              int64_t ld_gu, int64_t ld_p) {
+  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+    const bf16x8* gr = reinterpret_cast<const bf16x8*>(g + r * ld_gu);
+    const bf16x8* ur = reinterpret_cast<const bf16x8*>(u + r * ld_gu);
+    bf16x8* ar = reinterpret_cast<bf16x8*>(a + r * ld_p);
+    for (int i = threadIdx.x; i < cols_vec; i += 256) {
+      bf16x8 gv = gr[i], uv = ur[i], o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float z = (float)gv[e];
+        o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * (float)uv[e]);
+      }
+      ar[i] = o;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void swiglu_bwd_rows_kernel(const bf16_t* __restrict__ g, const bf16_t* __restrict__ u,
+                                                              const bf16_t* da, bf16_t* dg, bf16_t* __restrict__ du,
+                                                              int rows, int cols_vec, int64_t ld_gu, int64_t ld_p) {
+  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+    const bf16x8* gr = reinterpret_cast<const bf16x8*>(g + r * ld_gu);
+    const bf16x8* ur = reinterpret_cast<const bf16x8*>(u + r * ld_gu);
+    const bf16x8* dr = reinterpret_cast<const bf16x8*>(da + r * ld_p);
+    bf16x8* ogr = reinterpret_cast<bf16x8*>(dg + r * ld_p);
+    bf16x8* our = reinterpret_cast<bf16x8*>(du + r * ld_p);
+    for (int i = threadIdx.x; i < cols_vec; i += 256) {
+      bf16x8 gv = gr[i], uv = ur[i], dv = dr[i], og, ou;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float z = (float)gv[e], d = (float)dv[e];
+        const float sg = 1.0f / (1.0f + __expf(-z));
+        og[e] = (bf16_t)(d * (float)uv[e] * sg * (1.0f + z * (1.0f - sg)));
+        ou[e] = (bf16_t)(d * z * sg);
+      }
+      ogr[i] = og;
+      our[i] = ou;
+    }
+  }
+}
+
 static unsigned ew_blocks(int64_t nvec) {
   int64_t b = (nvec + 255) / 256;
   return (unsigned)(b < 256 * 16 ? (b > 0 ? b : 1) : 256 * 16);
@@ -325,13 +370,27 @@ int launch_swiglu_bwd(const void* g, const void* u, const void* da, int64_t n, v
   return check_launch("swiglu_backward");
 }
 
+int launch_swiglu_fwd_rows(const void* g, const void* u, int64_t rows, int64_t cols, int64_t ld_gu, void* a,
+                           int64_t ld_a, hipStream_t st) {
+  hipLaunchKernelGGL(swiglu_fwd_rows_kernel, dim3((unsigned)(rows < 8192 ? rows : 8192)), dim3(256), 0, st,
+                     (const bf16_t*)g, (const bf16_t*)u, (bf16_t*)a, (int)rows, (int)(cols / 8), ld_gu, ld_a);
+  return check_launch("swiglu_forward(rows)");
+}
+int launch_swiglu_bwd_rows(const void* g, const void* u, const void* da, int64_t rows, int64_t cols, int64_t ld_gu,
+                           int64_t ld_p, void* dg, void* du, hipStream_t st) {
+  hipLaunchKernelGGL(swiglu_bwd_rows_kernel, dim3((unsigned)(rows < 8192 ? rows : 8192)), dim3(256), 0, st,
+                     (const bf16_t*)g, (const bf16_t*)u, (const bf16_t*)da, (bf16_t*)dg, (bf16_t*)du, (int)rows,
+                     (int)(cols / 8), ld_gu, ld_p);
+  return check_launch("swiglu_backward(rows)");
+}
+
 // ------------------------------------------------------------------------------------------
 // bf16 transpose: out[c][r] = in[r][c], 64x64 tiles through LDS (16-byte global accesses on
 // both sides).  R and C are multiples of 64.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void transpose_kernel(const bf16_t* __restrict__ in,
                                                         bf16_t* __restrict__ out, int64_t R,
-                                                        int64_t C) {
+                                                        int64_t C, int64_t ld_out) {
   __shared__ bf16_t tile[64][66];
   const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
   const int t = threadIdx.x;
@@ -351,13 +410,13 @@ __global__ __launch_bounds__(256) void transpose_kernel(const bf16_t* __restrict
     bf16x8 v;
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = tile[rv + e][c];
-    *reinterpret_cast<bf16x8*>(out + (c0 + c) * R + r0 + rv) = v;
+    *reinterpret_cast<bf16x8*>(out + (c0 + c) * ld_out + r0 + rv) = v;
   }
 }
 
-int launch_transpose(const void* in, void* out, int64_t R, int64_t C, hipStream_t st) {
+int launch_transpose(const void* in, void* out, int64_t R, int64_t C, int64_t ld_out, hipStream_t st) {
   hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)(C / 64), (unsigned)(R / 64)), dim3(256), 0,
-                     st, (const bf16_t*)in, (bf16_t*)out, R, C);
+                     st, (const bf16_t*)in, (bf16_t*)out, R, C, ld_out);
   return check_launch("transpose");
 }
 

@@ -20,7 +20,13 @@ int launch_rope(void* z, int64_t batch, int64_t seq, int64_t n_heads, int64_t he
 int launch_swiglu_fwd(const void* g, const void* u, int64_t n, void* a, hipStream_t st);
 int launch_swiglu_bwd(const void* g, const void* u, const void* da, int64_t n, void* dg, void* du,
                       hipStream_t st);
-int launch_transpose(const void* in, void* out, int64_t R, int64_t C, hipStream_t st);
+// g, u: [rows, cols] with leading dimension ld_gu; a / da / dg / du with their own (padded) one
+int launch_swiglu_fwd_rows(const void* g, const void* u, int64_t rows, int64_t cols, int64_t ld_gu, void* a,
+                           int64_t ld_a, hipStream_t st);
+int launch_swiglu_bwd_rows(const void* g, const void* u, const void* da, int64_t rows, int64_t cols, int64_t ld_gu,
+                           int64_t ld_p, void* dg, void* du, hipStream_t st);
+// out[c][r] = in[r][c]; out has leading dimension ld_out >= R
+int launch_transpose(const void* in, void* out, int64_t R, int64_t C, int64_t ld_out, hipStream_t st);
 int launch_embed_fwd(const void* table, const int64_t* ids, int64_t T, int64_t V, int64_t D,
                      void* x0, hipStream_t st);
 int launch_embed_bwd(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D,
