@@ -310,6 +310,26 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16x8* g, const 
 
 // Row variants: g, u are [rows, cols] with leading dimension ld_gu, the other arrays with ld_p
 // (the layer keeps a, da/dg and du with padded rows).  One row per workgroup at a time.
+constexpr int SW_U = 4;   // 16-byte vectors per thread in flight
+__device__ __forceinline__ bf16x8 swiglu_vec(bf16x8 gv, bf16x8 uv) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float z = (float)gv[e];
+    o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * (float)uv[e]);
+  }
+  return o;
+}
+__device__ __forceinline__ void swiglu_grad_vec(bf16x8 gv, bf16x8 uv, bf16x8 dv, bf16x8& og, bf16x8& ou) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float z = (float)gv[e], d = (float)dv[e];
+    const float sg = 1.0f / (1.0f + __expf(-z));
+    og[e] = (bf16_t)(d * (float)uv[e] * sg * (1.0f + z * (1.0f - sg)));
+    ou[e] = (bf16_t)(d * z * sg);
+  }
+}
+
 __global__ __launch_bounds__(256) void swiglu_fwd_rows_kernel(const bf16_t* __restrict__ g, const bf16_t* __restrict__ u,
                                                               bf16_t* __restrict__ a, int rows, int cols_vec,
                                                               int64_t ld_gu, int64_t ld_p) {
@@ -317,14 +337,18 @@ __global__ __launch_bounds__(256) void swiglu_fwd_rows_kernel(const bf16_t* __re
     const bf16x8* gr = reinterpret_cast<const bf16x8*>(g + r * ld_gu);
     const bf16x8* ur = reinterpret_cast<const bf16x8*>(u + r * ld_gu);
     bf16x8* ar = reinterpret_cast<bf16x8*>(a + r * ld_p);
-    for (int i = threadIdx.x; i < cols_vec; i += 256) {
-      bf16x8 gv = gr[i], uv = ur[i], o;
+    for (int i0 = threadIdx.x; i0 < cols_vec; i0 += 256 * SW_U) {
+      bf16x8 gv[SW_U], uv[SW_U];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float z = (float)gv[e];
-        o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * (float)uv[e]);
+      for (int q = 0; q < SW_U; ++q) {
+        const int i = i0 + q * 256;
+        if (i < cols_vec) { gv[q] = __builtin_nontemporal_load(gr + i); uv[q] = __builtin_nontemporal_load(ur + i); }
       }
-      ar[i] = o;
+#pragma unroll
+      for (int q = 0; q < SW_U; ++q) {
+        const int i = i0 + q * 256;
+        if (i < cols_vec) ar[i] = swiglu_vec(gv[q], uv[q]);
+      }
     }
   }
 }
@@ -338,17 +362,25 @@ __global__ __launch_bounds__(256) void swiglu_bwd_rows_kernel(const bf16_t* __re
     const bf16x8* dr = reinterpret_cast<const bf16x8*>(da + r * ld_p);
     bf16x8* ogr = reinterpret_cast<bf16x8*>(dg + r * ld_p);
     bf16x8* our = reinterpret_cast<bf16x8*>(du + r * ld_p);
-    for (int i = threadIdx.x; i < cols_vec; i += 256) {
-      bf16x8 gv = gr[i], uv = ur[i], dv = dr[i], og, ou;
+    for (int i0 = threadIdx.x; i0 < cols_vec; i0 += 256 * SW_U) {
+      bf16x8 gv[SW_U], uv[SW_U], dv[SW_U];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float z = (float)gv[e], d = (float)dv[e];
-        const float sg = 1.0f / (1.0f + __expf(-z));
-        og[e] = (bf16_t)(d * (float)uv[e] * sg * (1.0f + z * (1.0f - sg)));
-        ou[e] = (bf16_t)(d * z * sg);
+      for (int q = 0; q < SW_U; ++q) {
+        const int i = i0 + q * 256;
+        if (i < cols_vec) {
+          gv[q] = __builtin_nontemporal_load(gr + i); uv[q] = __builtin_nontemporal_load(ur + i); dv[q] = dr[i];
+        }
       }
-      ogr[i] = og;
-      our[i] = ou;
+#pragma unroll
+      for (int q = 0; q < SW_U; ++q) {
+        const int i = i0 + q * 256;
+        if (i < cols_vec) {
+          bf16x8 og, ou;
+          swiglu_grad_vec(gv[q], uv[q], dv[q], og, ou);
+          ogr[i] = og;
+          our[i] = ou;
+        }
+      }
     }
   }
 }
