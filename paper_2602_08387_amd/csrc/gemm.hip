@@ -25,6 +25,7 @@
 // rows of C.
 #include "common.h"
 #include "kernels.h"
+#include <type_traits>
 
 namespace dl {
 
@@ -132,16 +133,48 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row0, int kk, 
     const int krow = MI == 32 ? kk * 16 + ((grp >> 1) << 3) + e : kk * 32 + (grp << 3) + e;
     const int f = (((krow & 3) << 2) | (((krow >> 3) & 1) << 1)) & (CPR - 1);  // same for krow and krow + 4
     const char* p0 = tile + krow * (R * 2) + ((((col >> 3) ^ f) << 4) | ((col & 7) << 1));
+    // Issued as inline assembly: for the builtin the compiler cannot tell that the read does not
+    // touch the stage the asynchronous global -> LDS loads are filling and puts an s_waitcnt vmcnt(0)
+    // in front of it, which stalls the loading waves for the whole load latency every K-step.  The
+    // price: the compiler does not count these reads in lgkmcnt either, so every consumer must sit
+    // behind wait_frags().
     bf16x8 v;
-    v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p0));
-    v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(p0 + 4 * R * 2));
+    bf16x4 lo, hi;
+    const uint32_t a0 = (uint32_t)(uintptr_t)(LDS_PTR(char))(p0);
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a0));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a0), "n"(4 * R * 2));
+    v.lo = lo;
+    v.hi = hi;
     return v;
+  }
+}
+
+// f(integral_constant<int, I>) for I = I0 .. N-1: a loop whose index is a compile-time constant
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
   }
 }
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Waits for every LDS read of this wave and makes the fragments depend on that wait, so that no
+// consumer of a fragment fetched by the inline-assembly transposed read can be scheduled before it.
+template <int FM, int FN>
+__device__ __forceinline__ void wait_frags(bf16x8 (&fa)[FM], bf16x8 (&fb)[FN]) {
+  static_assert(FM == 8 && FN == 4 || FM == 4 && FN == 4, "operand list written out for the two wave tiles in use");
+  if constexpr (FM == 8)
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fa[4]), "+v"(fa[5]), "+v"(fa[6]), "+v"(fa[7]),
+                   "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]), "+v"(fb[3]));
+  else
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]), "+v"(fb[3]));
 }
 
 // Position of the next tile pair to fetch: segment, k offset, and that segment's descriptors.
@@ -327,32 +360,33 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
 #pragma unroll
       for (int i = 0; i < FN; ++i) fb[0][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, 0, lane);
     }
+    if constexpr (!(AK && BKM)) wait_frags<FM, FN>(fa[0], fb[0]);
     for (int t = 0; t < total; ++t) {
       char* st_cur = smem + (t & 1) * STAGE;
       const char* ta = st_cur;
       const char* tb = ta + A_BYTES;
+      static_for<0, KK>([&](auto kk_c) {
+        constexpr int kk = decltype(kk_c)::value;
+        constexpr int cb = kk & 1, nb = cb ^ 1;
+        if constexpr (AK && BKM) {
+          if (kk + 1 < KK) {
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const int cb = kk & 1, nb = cb ^ 1;
-        if (kk + 1 < KK) {
+            for (int j = 0; j < FM; ++j) fa[nb][j] = read_frag<BM, AK>(ta, wave_m * TM + j * MI, kk + 1, lane);
 #pragma unroll
-          for (int j = 0; j < FM; ++j) fa[nb][j] = read_frag<BM, AK>(ta, wave_m * TM + j * MI, kk + 1, lane);
-#pragma unroll
-          for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, kk + 1, lane);
-        } else {
-          // all of this wave's reads of stage t are in registers; stage t+1 must have landed
-          wait_vmcnt<0>();   // the only loads in flight are those of stage t+1, issued one K-step ago
-          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-          __builtin_amdgcn_s_barrier();
-          asm volatile("" ::: "memory");
-          // every wave now holds its last fragments of stage t in registers: refill that stage with
-          // step t+2 right away, so the loads get a whole K-step to land (measured global -> LDS
-          // latency under load: about 1800 cycles against a K-step of about 3000)
-          if (loader) cur.issue_next(one, st_cur, wave, m0, n0, lane);
-          // k-major x k-major: the reads go out unconditionally (after the last K-step they fetch stale
-          // bytes nobody uses), which keeps them in one block with this group's MFMAs so that the
-          // scheduler interleaves them (+2 %); with transposed reads the burst is faster (measured)
-          if ((AK && BKM) || t + 1 < total) {
+            for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(tb, wave_n * TN + i * MI, kk + 1, lane);
+          } else {
+            // all of this wave's reads of stage t are in registers; stage t+1 must have landed
+            wait_vmcnt<0>();   // the only loads in flight are those of stage t+1, issued one K-step ago
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            // every wave now holds its last fragments of stage t in registers: refill that stage with
+            // step t+2 right away, so the loads get a whole K-step to land (measured global -> LDS
+            // latency under load: about 1800 cycles against a K-step of about 3000)
+            if (loader) cur.issue_next(one, st_cur, wave, m0, n0, lane);
+            // the reads go out unconditionally (after the last K-step they fetch stale bytes nobody
+            // uses), which keeps them in one block with this group's MFMAs so that the scheduler
+            // interleaves them (+2 %)
             const char* na = smem + ((t + 1) & 1) * STAGE;
             const char* nbp = na + A_BYTES;
 #pragma unroll
@@ -360,18 +394,54 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
 #pragma unroll
             for (int i = 0; i < FN; ++i) fb[nb][i] = read_frag<BN, BKM>(nbp, wave_n * TN + i * MI, 0, lane);
           }
+#pragma unroll
+          for (int i = 0; i < FN; ++i)
+#pragma unroll
+            for (int j = 0; j < FM; ++j)
+              acc[i][j] = mfma(fb[cb][i], fa[cb][j], acc[i][j]);
+#pragma unroll
+          for (int q = 0; q < FM + FN; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN) / (FM + FN), 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                      // DS read
+          }
+        } else {
+          // With a transposed operand the fragment reads are inline assembly (see read_frag), which the
+          // scheduler neither counts nor places, so the order is fixed by hand: the group's FN rows of
+          // MFMAs, each preceded by its share of the next fragments.  In the last group of a K-step the
+          // first row runs before the hand-over (it only needs registers), so the matrix pipe has
+          // work while the wave sits at the barrier.
+          constexpr bool last = kk + 1 == KK;
+          constexpr int NF = FM + FN;                       // fragments to fetch: A 0..FM-1, then B
+          constexpr int NCH = last ? FN - 1 : FN;           // chunks they are spread over
+          const char* ra_ = last ? smem + ((t + 1) & 1) * STAGE : ta;
+          const char* rb_ = ra_ + A_BYTES;
+          const bool do_reads = !last || t + 1 < total;
+#pragma unroll
+          for (int i = 0; i < FN; ++i) {
+            if (last && i == 1) {
+              wait_vmcnt<0>();   // stage t+1 has landed (loads issued one K-step ago)
+              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+              __builtin_amdgcn_s_barrier();
+              asm volatile("" ::: "memory");
+              if (loader) cur.issue_next(one, st_cur, wave, m0, n0, lane);   // step t+2 into the drained stage
+            }
+              const int ch = last ? i - 1 : i;
+            if (ch >= 0 && do_reads) {
+#pragma unroll
+              for (int f = ch * NF / NCH; f < (ch + 1) * NF / NCH; ++f) {
+                if (f < FM) fa[nb][f] = read_frag<BM, AK>(ra_, wave_m * TM + f * MI, last ? 0 : kk + 1, lane);
+                else fb[nb][f - FM] = read_frag<BN, BKM>(rb_, wave_n * TN + (f - FM) * MI, last ? 0 : kk + 1, lane);
+              }
+            }
+#pragma unroll
+            for (int j = 0; j < FM; ++j) acc[i][j] = mfma(fb[cb][i], fa[cb][j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          // the fragments fetched above are complete once this wait has passed; the next group's MFMAs
+          // depend on it
+          wait_frags<FM, FN>(fa[nb], fb[nb]);
         }
-#pragma unroll
-        for (int i = 0; i < FN; ++i)
-#pragma unroll
-          for (int j = 0; j < FM; ++j)
-            acc[i][j] = mfma(fb[cb][i], fa[cb][j], acc[i][j]);
-#pragma unroll
-        for (int q = 0; q < FM + FN; ++q) {
-          __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN) / (FM + FN), 0);  // MFMA
-          __builtin_amdgcn_sched_group_barrier(0x100, AK && BKM ? 1 : 2, 0);      // DS read
-        }
-      }
+      });
     }
     // (the hand-over of the last K-step waited for every load and passed a barrier after every wave's
     // last LDS read: the whole ring is free here)
