@@ -26,8 +26,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/
 # 8B-shaped layer), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain 1 GiB copy in the same
 # run (factors 2.0 and 1.0; profiles/layer_8b_hbm_traffic.txt).  Only valid for the GEMM source the
 # counters were taken on: reported as null when gemm.hip has changed since.
-GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "a307dc43796d8512ea846964c02bd2930968ef0652fec9124ca4cf62c22f9c43",
-                "fetch_bytes": 1.534e+09, "write_bytes": 2.024e+08}
+GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "01fbe9eb9df0d7f66bab715373a78fbd826279cbed12460867ddf7433685e412",
+                "fetch_bytes": 1.534e+09, "write_bytes": 2.013e+08}
 
 
 def _gemm_traffic(config_name):
