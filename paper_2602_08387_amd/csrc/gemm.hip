@@ -105,8 +105,14 @@ struct TileLoader {
 
   __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, char* lds_tile, int wave, int64_t ld,
                                         int k0) const {
+    issue_range<0, PER_WAVE>(rs, lds_tile, wave, ld, k0);
+  }
+  // this wave's loads I0 .. I1-1 of the tile
+  template <int I0, int I1>
+  __device__ __forceinline__ void issue_range(__amdgpu_buffer_rsrc_t rs, char* lds_tile, int wave, int64_t ld,
+                                              int k0) const {
 #pragma unroll
-    for (int i = 0; i < PER_WAVE; ++i) {
+    for (int i = I0; i < I1; ++i) {
       const int j = wave * PER_WAVE + i;
       const uint32_t soff = KMAJOR ? (uint32_t)(((int64_t)RPI * j * ld + k0) * 2)
                                    : (uint32_t)(((int64_t)(k0 + j * RPI) * ld) * 2);
@@ -204,6 +210,23 @@ struct LoadCursor {
   }
   __device__ __forceinline__ void open(const GemmKArgs& p, int s, int m0, int n0, int lane) {
     open_raw(p.a[s], p.b[s], p.lda[s], p.ldb[s], p.K[s], p.M, p.N, m0, n0, lane);
+  }
+  // The same in NC pieces (piece C of the A loads and of the B loads), so that a wave can spread its
+  // loads between MFMAs; the cursor moves on with the last piece.
+  template <int C, int NC>
+  __device__ __forceinline__ void issue_piece(const GemmKArgs& segs, char* stage, int wave, int m0, int n0, int lane) {
+    constexpr int PA = TileLoader<BM, AK, NW>::PER_WAVE, PB = TileLoader<BN, BKM, NW>::PER_WAVE;
+    if (seg < nseg) {
+      la.template issue_range<C * PA / NC, (C + 1) * PA / NC>(ra, stage, wave, lda, k);
+      lb.template issue_range<C * PB / NC, (C + 1) * PB / NC>(rb, stage + BM * BK * 2, wave, ldb, k);
+      if constexpr (C + 1 == NC) {
+        k += BK;
+        if (k == kend) {
+          k = 0;
+          if (++seg < nseg) open(segs, seg, m0, n0, lane);
+        }
+      }
+    }
   }
   // `segs`: the problem whose further K-segments follow (only read when nseg > 1)
   __device__ __forceinline__ void issue_next(const GemmKArgs& segs, char* stage, int wave, int m0, int n0, int lane) {
@@ -411,19 +434,25 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
           // first row runs before the hand-over (it only needs registers), so the matrix pipe has
           // work while the wave sits at the barrier.
           constexpr bool last = kk + 1 == KK;
+          // the refill of the drained stage is spread over the rows after the hand-over: a wave is held
+          // for some 27 cycles per load instruction, which its own queued MFMAs then cover (-0.15 ms)
+          constexpr bool GEMM_SPREAD_LOADS = true;
           constexpr int NF = FM + FN;                       // fragments to fetch: A 0..FM-1, then B
           constexpr int NCH = last ? FN - 1 : FN;           // chunks they are spread over
           const char* ra_ = last ? smem + ((t + 1) & 1) * STAGE : ta;
           const char* rb_ = ra_ + A_BYTES;
           const bool do_reads = !last || t + 1 < total;
-#pragma unroll
-          for (int i = 0; i < FN; ++i) {
+          static_for<0, FN>([&](auto i_c) {
+            constexpr int i = decltype(i_c)::value;
             if (last && i == 1) {
               wait_vmcnt<0>();   // stage t+1 has landed (loads issued one K-step ago)
               asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
               __builtin_amdgcn_s_barrier();
               asm volatile("" ::: "memory");
-              if (loader) cur.issue_next(one, st_cur, wave, m0, n0, lane);   // step t+2 into the drained stage
+              if (!GEMM_SPREAD_LOADS && loader) cur.issue_next(one, st_cur, wave, m0, n0, lane);   // step t+2 into the drained stage
+            }
+            if constexpr (GEMM_SPREAD_LOADS && last && i >= 1) {
+              if (loader) cur.template issue_piece<i - 1, FN - 1>(one, st_cur, wave, m0, n0, lane);
             }
               const int ch = last ? i - 1 : i;
             if (ch >= 0 && do_reads) {
@@ -436,7 +465,7 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
 #pragma unroll
             for (int j = 0; j < FM; ++j) acc[i][j] = mfma(fb[cb][i], fa[cb][j], acc[i][j]);
             __builtin_amdgcn_sched_barrier(0);
-          }
+          });
           // the fragments fetched above are complete once this wait has passed; the next group's MFMAs
           // depend on it
           wait_frags<FM, FN>(fa[nb], fb[nb]);
