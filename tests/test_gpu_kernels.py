@@ -99,7 +99,10 @@ def test_swiglu(K):
 # ------------------------------------------------------------------ linear layers (the MFMA GEMM)
 @pytest.mark.parametrize("T,Kd,N,res", [
     (128, 128, 128, False), (200, 64, 72, True), (512, 768, 2304, False), (1000, 2048, 1024, True),
-    (2048, 4096, 4096, False), (4096, 1024, 5632, True)])
+    (2048, 4096, 4096, False), (4096, 1024, 5632, True),
+    # more 256x256 tiles than CUs with ragged last tile rows and columns: every persistent workgroup
+    # walks several tiles, some of them partly outside the matrix
+    (5000, 512, 5064, True), (4100, 256, 4360, False)])
 def test_linear_forward(K, T, Kd, N, res):
     rng = np.random.default_rng(T + N)
     xb, wb, rb = _rand_bits(rng, (T, Kd)), _rand_bits(rng, (N, Kd), 0.05), _rand_bits(rng, (T, N))
@@ -115,7 +118,7 @@ def test_linear_forward(K, T, Kd, N, res):
 
 
 @pytest.mark.parametrize("T,Kd,N", [(128, 128, 128), (192, 64, 320), (1024, 768, 2048), (2048, 2048, 5632),
-                                     (4096, 4096, 1024)])
+                                     (4096, 4096, 1024), (4160, 4416, 4288)])
 def test_linear_backward(K, T, Kd, N):
     rng = np.random.default_rng(T + N + 1)
     xb, wb, db = _rand_bits(rng, (T, Kd)), _rand_bits(rng, (N, Kd), 0.05), _rand_bits(rng, (T, N))
