@@ -138,6 +138,14 @@ int rmsnorm_backward(const void* x, const void* gamma, const float* rstd, const 
 int linear_forward(const void* x, const void* w, const void* residual, int64_t T, int64_t K,
                    int64_t N, void* y, void* stream);
 
+/* The gated pair of the SwiGLU MLP of the transformer block (Fig. 2; Training Pipeline paragraph): g = x Wg^T, u = x Wu^T, a = silu(g) * u, the
+ * activation taken from g and u as stored (rounded to bf16), so a equals swiglu_forward(g, u) bit
+ * for bit.  x [T, K], w_gate and w_up [F, K], g, u, a [T, F] dense; all bf16.  K % 64 == 0,
+ * F % 8 == 0.  Large problems run as one kernel whose epilogue applies the activation; small ones
+ * as two products and the activation kernel.                                                   */
+int linear_swiglu_forward(const void* x, const void* w_gate, const void* w_up, int64_t T, int64_t K,
+                          int64_t F, void* g, void* u, void* a, void* stream);
+
 /* Gradients of y = x W^T: dx = dy W ([T, K], skipped if dx == NULL) and dw = dy^T x ([N, K],
  * skipped if dw == NULL).  T, K, N multiples of 64.  workspace (device, needed when dx is
  * asked for: it receives a transposed copy of w): linear_backward_workspace_bytes(T, K, N).   */

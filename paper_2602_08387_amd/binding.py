@@ -13,7 +13,7 @@ EXPORTED_SYMBOLS = (
     "dlayer_version", "dlayer_last_error", "dlayer_saved_bytes", "dlayer_workspace_bytes",
     "dlayer_forward", "dlayer_backward", "ce_loss_workspace_bytes", "ce_loss_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward_workspace_bytes", "rmsnorm_backward",
-    "linear_forward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
+    "linear_forward", "linear_swiglu_forward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
     "attention_forward", "attention_backward_workspace_bytes", "attention_backward",
     "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",
 )
@@ -64,6 +64,7 @@ def _load():
         "rmsnorm_backward_workspace_bytes": (sz, [i64, i64]),
         "rmsnorm_backward": (C.c_int, [vp, vp, vp, vp, vp, i64, i64, vp, vp, C.c_int, vp, vp]),
         "linear_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp]),
+        "linear_swiglu_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]),
         "linear_backward_workspace_bytes": (sz, [i64, i64, i64]),
         "linear_backward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp, C.c_int, vp, vp]),
         "linear_wgrad_group": (C.c_int, [i32, vp, vp, vp, vp, i64, vp, C.c_int, vp]),
@@ -170,6 +171,11 @@ def linear_backward_workspace_bytes(T, K, N) -> int:
 def linear_backward(x, w, dy, T, K, N, dx, dw, accumulate_dw, workspace, stream=None):
     _check(lib.linear_backward(_p(x), _p(w), _p(dy), T, K, N, _p(dx), _p(dw), int(accumulate_dw),
                                _p(workspace), _stream(stream)), "linear_backward")
+
+
+def linear_swiglu_forward(x, w_gate, w_up, T, K, F, g, u, a, stream=None):
+    _check(lib.linear_swiglu_forward(_p(x), _p(w_gate), _p(w_up), T, K, F, _p(g), _p(u), _p(a), _stream(stream)),
+           "linear_swiglu_forward")
 
 
 def linear_wgrad_group(dys, xs, Ns, Ks, T, dws, accumulate_dw, stream=None):

@@ -148,6 +148,17 @@ static int gemm_nt(const void* x, int64_t ldx, const void* w, const void* res, i
 }
 // dx[T,K] = sum_s dy_s[T,N_s] WT_s[K,N_s]^T with the transposed weights WT_s = W_s^T; ld: leading
 // dimension of every dy_s and WT_s, lddx: that of dx
+// g = x Wg^T, u = x Wu^T, a = silu(g) * u (a with leading dimension lda): one fused launch when the
+// problem fills the chip with 256 x 256 tiles, otherwise two products and the activation kernel.
+// Both routes give the same bits (the fused epilogue applies the activation to the rounded g, u).
+static int gate_up_swiglu(const void* x, const void* wg, const void* wu, int64_t T, int64_t K, int64_t F, void* g,
+                          void* u, void* a, int64_t lda, hipStream_t st) {
+  if (gemm_swiglu_applies(T, F)) return launch_gemm_swiglu(x, K, wg, wu, K, T, K, F, g, u, F, a, lda, st);
+  TRY(gemm_nt(x, K, wg, nullptr, T, K, F, g, st));
+  TRY(gemm_nt(x, K, wu, nullptr, T, K, F, u, st));
+  return launch_swiglu_fwd_rows(g, u, T, F, F, a, lda, st);
+}
+
 static int gemm_dgrad_t(int nseg, const void* const* dy, const void* const* wt, const int64_t* Ns, int64_t ld,
                         int64_t T, int64_t K, void* dx, int64_t lddx, hipStream_t st) {
   GemmArgs g{};
@@ -213,10 +224,8 @@ int dlayer_forward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w
   TRY(launch_attention_fwd(s.q, s.k, s.v, B, S, Hq, Hkv, dh, s.o, s.lse, st));
   TRY(gemm_nt(s.o, QD, w->wo, x, T, QD, D, s.y1, st));
   TRY(launch_rmsnorm_fwd(s.y1, w->g_mlp, T, D, cfg->rms_eps, s.h2, s.rstd2, st));
-  TRY(gemm_nt(s.h2, D, w->w_gate, nullptr, T, D, F, s.g, st));
-  TRY(gemm_nt(s.h2, D, w->w_up, nullptr, T, D, F, s.u, st));
   const int64_t Fp = padded_ff(cfg);
-  TRY(launch_swiglu_fwd_rows(s.g, s.u, T, F, F, s.a, Fp, st));
+  TRY(gate_up_swiglu(s.h2, w->w_gate, w->w_up, T, D, F, s.g, s.u, s.a, Fp, st));
   TRY(gemm_nt(s.a, Fp, w->w_down, s.y1, T, F, D, y, st));
   return DLAYER_OK;
 }
@@ -328,6 +337,17 @@ int linear_forward(const void* x, const void* w, const void* residual, int64_t T
   REQUIRE(residual == nullptr || aligned16(residual), "linear_forward: residual is misaligned");
   TRY(check_device());
   return gemm_nt(x, K, w, residual, T, K, N, y, (hipStream_t)stream);
+}
+
+int linear_swiglu_forward(const void* x, const void* w_gate, const void* w_up, int64_t T, int64_t K, int64_t F,
+                          void* g, void* u, void* a, void* stream) {
+  REQUIRE(T > 0 && K > 0 && F > 0 && K % 64 == 0 && F % 8 == 0,
+          "linear_swiglu_forward: need K %% 64 == 0 and F %% 8 == 0");
+  REQUIRE(T * K * 2 < ((int64_t)1 << 32) && F * K * 2 < ((int64_t)1 << 32) && T < (1 << 30) && F < (1 << 29),
+          "linear_swiglu_forward: an operand reaches 4 GiB");
+  REQUIRE_PTR(x); REQUIRE_PTR(w_gate); REQUIRE_PTR(w_up); REQUIRE_PTR(g); REQUIRE_PTR(u); REQUIRE_PTR(a);
+  TRY(check_device());
+  return gate_up_swiglu(x, w_gate, w_up, T, K, F, g, u, a, F, (hipStream_t)stream);
 }
 
 size_t linear_backward_workspace_bytes(int64_t T, int64_t K, int64_t N) {

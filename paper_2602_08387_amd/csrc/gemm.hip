@@ -58,6 +58,10 @@ struct GemmKArgs {
   const bf16_t* r;
   int accumulate;
   int tiles_m, tiles_n;
+  // gated-pair products only (see gemm_swiglu_kernel): second weight, second and third output
+  const bf16_t* b2;
+  bf16_t *c2, *c3;
+  int64_t ldc3;
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
@@ -122,6 +126,24 @@ struct TileLoader {
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, vo, soff, 0, 0);
     }
   }
+  // Tile of a PAIR of k-major matrices: of every 64 tile rows the first 32 are rows of the first
+  // matrix and the next 32 the SAME rows of the second (tile row r <- matrix (r / 32) & 1, row
+  // (r / 64) * 32 + r % 32), so that a wave whose MFMA tile spans 64 of these rows holds both values
+  // of a column pair.  LDS placement and swizzle are those of the plain tile.
+  template <int I0, int I1>
+  __device__ __forceinline__ void issue_pair_range(__amdgpu_buffer_rsrc_t rs0, __amdgpu_buffer_rsrc_t rs1,
+                                                   char* lds_tile, int wave, int64_t ld, int k0) const {
+    static_assert(KMAJOR && 32 % RPI == 0, "an instruction's rows must lie in one matrix");
+#pragma unroll
+    for (int i = I0; i < I1; ++i) {
+      const int j = wave * PER_WAVE + i;
+      const int r0 = j * RPI;
+      const int row = (r0 >> 6) * 32 + (r0 & 31);
+      const uint32_t soff = (uint32_t)(((int64_t)row * ld + k0) * 2);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(((r0 >> 5) & 1) ? rs1 : rs0, (LDS_PTR(void))(lds_tile + j * 1024), 16,
+                                               voff[i % NVAR], soff, 0, 0);
+    }
+  }
 };
 
 // MFMA operand fragment for MI rows starting at row0 (tile-local M/N index), k-substep kk (KSTEP k).
@@ -184,11 +206,13 @@ __device__ __forceinline__ void wait_frags(bf16x8 (&fa)[FM], bf16x8 (&fb)[FN]) {
 }
 
 // Position of the next tile pair to fetch: segment, k offset, and that segment's descriptors.
-template <int BM, int BN, int NW, bool AK, bool BKM>
+// PAIR: the B tile interleaves two weight matrices (TileLoader::issue_pair_range); n0 and N then
+// count columns of the interleaved product, twice the rows of either matrix.
+template <int BM, int BN, int NW, bool AK, bool BKM, bool PAIR = false>
 struct LoadCursor {
   TileLoader<BM, AK, NW> la;
   TileLoader<BN, BKM, NW> lb;
-  __amdgpu_buffer_rsrc_t ra, rb;
+  __amdgpu_buffer_rsrc_t ra, rb, rb2;
   int64_t lda, ldb;
   int seg = 0, k = 0, kend = 0, nseg = 1;   // kend: K of the open segment (kept in a register: no kernarg read per K-step)
 
@@ -208,6 +232,12 @@ struct LoadCursor {
     la.init(lane, lda);
     lb.init(lane, ldb);
   }
+  __device__ __forceinline__ void open_pair(const bf16_t* a, const bf16_t* b, const bf16_t* b2, int64_t lda_,
+                                            int64_t ldb_, int K, int M, int N, int m0, int n0, int lane) {
+    static_assert(!PAIR || (AK && BKM), "paired weights are k-major");
+    open_raw(a, b, lda_, ldb_, K, M, N / 2, m0, n0 / 2, lane);
+    rb2 = make_rsrc(b2 + (int64_t)(n0 / 2) * ldb_, (uint32_t)((((int64_t)(N / 2 - n0 / 2 - 1)) * ldb_ + K) * 2));
+  }
   __device__ __forceinline__ void open(const GemmKArgs& p, int s, int m0, int n0, int lane) {
     open_raw(p.a[s], p.b[s], p.lda[s], p.ldb[s], p.K[s], p.M, p.N, m0, n0, lane);
   }
@@ -218,7 +248,10 @@ struct LoadCursor {
     constexpr int PA = TileLoader<BM, AK, NW>::PER_WAVE, PB = TileLoader<BN, BKM, NW>::PER_WAVE;
     if (seg < nseg) {
       la.template issue_range<C * PA / NC, (C + 1) * PA / NC>(ra, stage, wave, lda, k);
-      lb.template issue_range<C * PB / NC, (C + 1) * PB / NC>(rb, stage + BM * BK * 2, wave, ldb, k);
+      if constexpr (PAIR)
+        lb.template issue_pair_range<C * PB / NC, (C + 1) * PB / NC>(rb, rb2, stage + BM * BK * 2, wave, ldb, k);
+      else
+        lb.template issue_range<C * PB / NC, (C + 1) * PB / NC>(rb, stage + BM * BK * 2, wave, ldb, k);
       if constexpr (C + 1 == NC) {
         k += BK;
         if (k == kend) {
@@ -232,7 +265,10 @@ struct LoadCursor {
   __device__ __forceinline__ void issue_next(const GemmKArgs& segs, char* stage, int wave, int m0, int n0, int lane) {
     if (seg < nseg) {
       la.issue(ra, stage, wave, lda, k);
-      lb.issue(rb, stage + BM * BK * 2, wave, ldb, k);
+      if constexpr (PAIR)
+        lb.template issue_pair_range<0, TileLoader<BN, BKM, NW>::PER_WAVE>(rb, rb2, stage + BM * BK * 2, wave, ldb, k);
+      else
+        lb.issue(rb, stage + BM * BK * 2, wave, ldb, k);
       k += BK;
       if (k == kend) {
         k = 0;
@@ -266,7 +302,12 @@ struct GemmGroupKArgs {
 // The kernel arguments are only ever read with compile-time offsets (a grouped launch picks its
 // problem by comparing against each index in turn): a run-time index into the argument block would
 // make the compiler copy the whole block to scratch memory and read it back through vector loads.
-template <bool GROUPED, int BM, int BN, int WM, int WN, bool AK, bool BKM>
+//
+// SWIGLU: the gated pair of the MLP in one pass.  B interleaves the rows of two weight matrices
+// (LoadCursor PAIR) so that every wave holds g = x Wg^T and u = x Wu^T for the same 32 columns; the
+// epilogue stores g to c, u to c2 and silu(g) * u, taken from the ROUNDED g and u like the separate
+// activation kernel would, to c3.  M x N is the interleaved product: N = twice the columns of g.
+template <bool GROUPED, int BM, int BN, int WM, int WN, bool AK, bool BKM, bool SWIGLU = false>
 __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const GemmKArgs& one) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
@@ -300,7 +341,8 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
   // What the epilogue needs of a tile's problem, by value (the next tile's cursor is opened before the
   // current tile's epilogue runs).
   struct Tile { int m0, n0, total, M, N, accumulate; bf16_t* c; const bf16_t* r; int64_t ldc; };
-  LoadCursor<BM, BN, NL, AK, BKM> cur;
+  LoadCursor<BM, BN, NL, AK, BKM, SWIGLU> cur;
+  static_assert(!SWIGLU || (!GROUPED && TN == 64 && MI == 16), "gated pair: one 64-column strip per wave");
 
   // tile id -> tile origin, and the load cursor opened on the tile's first K-segment.  The tile
   // sequence of a problem runs in bands of 8 tile-rows, so that the ~32 consecutive tiles an XCD holds
@@ -340,7 +382,8 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
     t.n0 = (in_band / band_h) * BN;
     cur.seg = 0;
     cur.k = 0;
-    cur.open_raw(a0, b0, lda0, ldb0, K0, t.M, t.N, t.m0, t.n0, lane);
+    if constexpr (SWIGLU) cur.open_pair(a0, b0, one.b2, lda0, ldb0, K0, t.M, t.N, t.m0, t.n0, lane);
+    else cur.open_raw(a0, b0, lda0, ldb0, K0, t.M, t.N, t.m0, t.n0, lane);
     return t;
   };
 
@@ -503,6 +546,57 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
       const int n = i * MI + (MI == 32 ? g * 8 + lq * 4 : lq * 4);
       return row * 128 + ((((n >> 3) ^ ((row >> 1) & 7)) << 4) | ((n & 4) << 1));
     };
+    if constexpr (SWIGLU) {
+      // staged columns 0..31 are g, 32..63 are u, both for columns nh .. nh+31 of their matrices
+      const int nh = n0 / 2 + wave_n * 32, NH = p.N / 2;
+#pragma unroll
+      for (int hf = 0; hf < 4; ++hf) {
+        const int mbase = m0 + wave_m * TM + hf * HM;
+#pragma unroll
+        for (int jj = 0; jj < HF; ++jj)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[i][hf * HF + jj][e];
+            *reinterpret_cast<bf16x4*>(stg + stg_off(jj, i, 0)) = o;
+          }
+        if (hf == 0 && more) {
+          if (tl.total >= 2) wait_vmcnt<LPW>(); else wait_vmcnt<0>();
+        }
+#pragma unroll
+        for (int t = 0; t < HM / 8; ++t) {
+          const int row = t * 8 + rrow;
+          const int m = mbase + row;
+          const int cl = (rpc ^ ((row >> 1) & 7)) << 3;
+          const int n = nh + (cl & 31);
+          const bf16x8 v = *reinterpret_cast<const bf16x8*>(stg + row * 128 + (rpc << 4));
+          bf16_t* dst = cl >= 32 ? one.c2 : p.c;
+          if (m < p.M && n < NH) *reinterpret_cast<bf16x8*>(dst + (int64_t)m * p.ldc + n) = v;
+        }
+#pragma unroll
+        for (int jj = 0; jj < HF; ++jj)
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float z = (float)(bf16_t)acc[i][hf * HF + jj][e];
+              o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * (float)(bf16_t)acc[i + 2][hf * HF + jj][e]);
+            }
+            *reinterpret_cast<bf16x4*>(stg + stg_off(jj, i, 0)) = o;
+          }
+#pragma unroll
+        for (int t = 0; t < HM / 8; ++t) {
+          const int row = t * 8 + rrow;
+          const int m = mbase + row;
+          const int cl = (rpc ^ ((row >> 1) & 7)) << 3;
+          const int n = nh + cl;
+          const bf16x8 v = *reinterpret_cast<const bf16x8*>(stg + row * 128 + (rpc << 4));
+          if (cl < 32 && m < p.M && n < NH) *reinterpret_cast<bf16x8*>(one.c3 + (int64_t)m * one.ldc3 + n) = v;
+        }
+      }
+    } else {
 #pragma unroll
     for (int nb = 0; nb < TN / 64; ++nb) {
       const int nbase = n0 + wave_n * TN + nb * 64;
@@ -558,6 +652,7 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
         }
       }
     }
+    }
     if (!more) break;
   }
 }
@@ -565,6 +660,11 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   gemm_persistent<false, BM, BN, WM, WN, AK, BKM>(GemmGroupKArgs{}, p);
+}
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_swiglu_kernel(const GemmKArgs p) {
+  gemm_persistent<false, BM, BN, WM, WN, true, true, true>(GemmGroupKArgs{}, p);
 }
 
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
@@ -674,6 +774,44 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   const int64_t tiles256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
   if (tiles256 >= 192) return launch_cfg<256, 256, 2, 4>(k, g.a_kmajor, g.b_kmajor, st);
   return launch_cfg<128, 128, 2, 2>(k, g.a_kmajor, g.b_kmajor, st);
+}
+
+bool gemm_swiglu_applies(int64_t T, int64_t F) {
+  return F % 8 == 0 && ((T + 255) / 256) * ((2 * F + 255) / 256) >= 192;
+}
+
+int launch_gemm_swiglu(const void* x, int64_t ldx, const void* wg, const void* wu, int64_t ldw, int64_t T, int64_t K,
+                       int64_t F, void* g, void* u, int64_t ldgu, void* a, int64_t lda, hipStream_t st) {
+  if (!gemm_swiglu_applies(T, F)) return fail(-1, "gemm swiglu: shape T=%lld F=%lld not served by the fused kernel", (long long)T, (long long)F);
+  constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
+  GemmKArgs k{};
+  k.nseg = 1;
+  k.a[0] = (const bf16_t*)x;
+  k.b[0] = (const bf16_t*)wg;
+  k.b2 = (const bf16_t*)wu;
+  k.lda[0] = ldx;
+  k.ldb[0] = ldw;
+  k.K[0] = (int)K;
+  k.M = (int)T;
+  k.N = (int)(2 * F);
+  k.c = (bf16_t*)g;
+  k.c2 = (bf16_t*)u;
+  k.ldc = ldgu;
+  k.c3 = (bf16_t*)a;
+  k.ldc3 = lda;
+  k.tiles_m = (k.M + BM - 1) / BM;
+  k.tiles_n = (k.N + BN - 1) / BN;
+  const dim3 grid((unsigned)persistent_grid(k.tiles_m * k.tiles_n)), block(WM * WN * 64);
+  const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
+  auto kern = gemm_swiglu_kernel<BM, BN, WM, WN>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return fail(-3, "gemm: cannot reserve %zu B of LDS: %s", lds, hipGetErrorString(e));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, block, lds, st, k);
+  return check_launch("gemm swiglu");
 }
 
 int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st) {

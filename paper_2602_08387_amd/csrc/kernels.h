@@ -57,6 +57,12 @@ int launch_gemm(const GemmArgs& g, hipStream_t st);
 // Up to 8 independent problems with the same a_kmajor/b_kmajor in one launch (only the layout of
 // the weight-gradient product, both operands mn-major, is built).
 int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st);
+// g = x Wg^T, u = x Wu^T and a = silu(g) * u (from the rounded g, u) in one launch.  x [T, K] with
+// leading dimension ldx, wg and wu [F, K] with ldw, g and u with ldgu, a with lda.  Only shapes
+// gemm_swiglu_applies() accepts (enough 256 x 256 tiles to fill the chip).
+bool gemm_swiglu_applies(int64_t T, int64_t F);
+int launch_gemm_swiglu(const void* x, int64_t ldx, const void* wg, const void* wu, int64_t ldw, int64_t T, int64_t K,
+                       int64_t F, void* g, void* u, int64_t ldgu, void* a, int64_t lda, hipStream_t st);
 
 // ---- attention.hip
 int launch_attention_fwd(const void* q, const void* k, const void* v, int64_t B, int64_t S,

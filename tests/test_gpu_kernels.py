@@ -158,6 +158,33 @@ def test_linear_wgrad_group(K):
         K.linear_wgrad_group(dyd[:1], xd[:1], [100], [256], T, dws[:1], 0)
 
 
+@pytest.mark.parametrize("T,Kd,F", [
+    (256, 128, 512),        # small: two products and the activation kernel
+    (1024, 256, 6144),      # 192 tiles of 256 x 256: the fused kernel
+    (1000, 192, 6152),      # fused, ragged in T and F (F not a multiple of the 128-column half tile)
+    (2304, 128, 8200),      # fused, more tiles than CUs (a workgroup walks several), ragged F
+])
+def test_linear_swiglu_forward(K, T, Kd, F):
+    """The gated pair g = x Wg^T, u = x Wu^T, a = silu(g) u in one call: against the oracle, and bit
+    for bit against the two products and the activation launched separately."""
+    rng = np.random.default_rng(T + F)
+    xb, gb, ub = _rand_bits(rng, (T, Kd)), _rand_bits(rng, (F, Kd), 0.1), _rand_bits(rng, (F, Kd), 0.1)
+    x, wg, wu = map(si.bf16_bits_to_f64, (xb, gb, ub))
+    xd, wgd, wud = map(dev_bf16, (xb, gb, ub))
+    g, u, a = (torch.full((T, F), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    K.linear_swiglu_forward(xd, wgd, wud, T, Kd, F, g, u, a)
+    g_ref, u_ref = x @ wg.T, x @ wu.T
+    assert_close(g, g_ref, "g", rel_tol=8e-3)
+    assert_close(u, u_ref, "u", rel_tol=8e-3)
+    assert_close(a, odl.swiglu_fwd(g_ref, u_ref), "a", rel_tol=1.2e-2)
+    g2, u2, a2 = (torch.full((T, F), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    K.linear_forward(xd, wgd, None, T, Kd, F, g2)
+    K.linear_forward(xd, wud, None, T, Kd, F, u2)
+    K.swiglu_forward(g2, u2, T * F, a2)
+    for name, p, q in (("g", g, g2), ("u", u, u2), ("a", a, a2)):
+        assert torch.equal(p.view(torch.int16), q.view(torch.int16)), f"{name}: fused and separate launches differ"
+
+
 @pytest.mark.parametrize("Kd,N,res", [(4096, 14336, False), (14336, 4096, True)])
 def test_linear_full_size_sampled(K, Kd, N, res):
     """The two widest projections of the 8B-shaped layer at their full size (T = 16384), as the
