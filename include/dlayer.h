@@ -146,6 +146,17 @@ int linear_forward(const void* x, const void* w, const void* residual, int64_t T
 int linear_swiglu_forward(const void* x, const void* w_gate, const void* w_up, int64_t T, int64_t K,
                           int64_t F, void* g, void* u, void* a, void* stream);
 
+/* Backward of y = a W_down^T with a = silu(g) * u, as far as g and u: da = dy W_down, then
+ * (dg, du) = swiglu_backward(g, u, da) for da rounded to bf16, so the result equals
+ * linear_backward (dx only) followed by swiglu_backward bit for bit; large problems run as one
+ * kernel that never stores da.  dy [T, D], w_down [D, F], g, u, dg, du [T, F] dense; all bf16.
+ * T, D, F multiples of 64.  workspace (device; receives a transposed copy of w_down):
+ * linear_swiglu_backward_workspace_bytes(T, D, F).                                             */
+size_t linear_swiglu_backward_workspace_bytes(int64_t T, int64_t D, int64_t F);
+int linear_swiglu_backward(const void* dy, const void* w_down, const void* g, const void* u,
+                           int64_t T, int64_t D, int64_t F, void* dg, void* du, void* workspace,
+                           void* stream);
+
 /* Gradients of y = x W^T: dx = dy W ([T, K], skipped if dx == NULL) and dw = dy^T x ([N, K],
  * skipped if dw == NULL).  T, K, N multiples of 64.  workspace (device, needed when dx is
  * asked for: it receives a transposed copy of w): linear_backward_workspace_bytes(T, K, N).   */

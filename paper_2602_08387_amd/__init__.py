@@ -15,7 +15,8 @@ _BINDING_NAMES = (
     "dlayer_version", "dlayer_saved_bytes", "dlayer_workspace_bytes", "dlayer_forward", "dlayer_backward",
     "ce_loss_workspace_bytes", "ce_loss_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward", "rmsnorm_backward_workspace_bytes",
-    "linear_forward", "linear_swiglu_forward", "linear_backward", "linear_backward_workspace_bytes", "linear_wgrad_group",
+    "linear_forward", "linear_swiglu_forward", "linear_swiglu_backward",
+    "linear_swiglu_backward_workspace_bytes", "linear_backward", "linear_backward_workspace_bytes", "linear_wgrad_group",
     "rope_apply", "attention_forward", "attention_backward", "attention_backward_workspace_bytes",
     "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",
     "EXPORTED_SYMBOLS", "WEIGHT_FIELDS",

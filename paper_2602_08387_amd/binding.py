@@ -13,7 +13,8 @@ EXPORTED_SYMBOLS = (
     "dlayer_version", "dlayer_last_error", "dlayer_saved_bytes", "dlayer_workspace_bytes",
     "dlayer_forward", "dlayer_backward", "ce_loss_workspace_bytes", "ce_loss_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward_workspace_bytes", "rmsnorm_backward",
-    "linear_forward", "linear_swiglu_forward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
+    "linear_forward", "linear_swiglu_forward", "linear_swiglu_backward_workspace_bytes",
+    "linear_swiglu_backward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
     "attention_forward", "attention_backward_workspace_bytes", "attention_backward",
     "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",
 )
@@ -65,6 +66,8 @@ def _load():
         "rmsnorm_backward": (C.c_int, [vp, vp, vp, vp, vp, i64, i64, vp, vp, C.c_int, vp, vp]),
         "linear_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp]),
         "linear_swiglu_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]),
+        "linear_swiglu_backward_workspace_bytes": (C.c_size_t, [i64, i64, i64]),
+        "linear_swiglu_backward": (C.c_int, [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]),
         "linear_backward_workspace_bytes": (sz, [i64, i64, i64]),
         "linear_backward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp, C.c_int, vp, vp]),
         "linear_wgrad_group": (C.c_int, [i32, vp, vp, vp, vp, i64, vp, C.c_int, vp]),
@@ -176,6 +179,15 @@ def linear_backward(x, w, dy, T, K, N, dx, dw, accumulate_dw, workspace, stream=
 def linear_swiglu_forward(x, w_gate, w_up, T, K, F, g, u, a, stream=None):
     _check(lib.linear_swiglu_forward(_p(x), _p(w_gate), _p(w_up), T, K, F, _p(g), _p(u), _p(a), _stream(stream)),
            "linear_swiglu_forward")
+
+
+def linear_swiglu_backward_workspace_bytes(T, D, F) -> int:
+    return lib.linear_swiglu_backward_workspace_bytes(T, D, F)
+
+
+def linear_swiglu_backward(dy, w_down, g, u, T, D, F, dg, du, workspace, stream=None):
+    _check(lib.linear_swiglu_backward(_p(dy), _p(w_down), _p(g), _p(u), T, D, F, _p(dg), _p(du), _p(workspace),
+                                      _stream(stream)), "linear_swiglu_backward")
 
 
 def linear_wgrad_group(dys, xs, Ns, Ks, T, dws, accumulate_dw, stream=None):

@@ -168,6 +168,17 @@ static int gemm_dgrad_t(int nseg, const void* const* dy, const void* const* wt, 
   g.a_kmajor = true; g.b_kmajor = true;
   return launch_gemm(g, st);
 }
+
+// da = dy Wd for the transposed copy wdT [F, D], then (dg, du) = SwiGLU gradient; dg, du with leading
+// dimension ldd.  One fused launch when the problem fills the chip, otherwise the product into dg
+// followed by the activation-gradient kernel in place; same bits either way.
+static int down_dgrad_swiglu(const void* dy, const void* wdT, int64_t T, int64_t D, int64_t F, const void* g,
+                             const void* u, void* dg, void* du, int64_t ldd, hipStream_t st) {
+  if (gemm_swiglu_grad_applies(T, F)) return launch_gemm_swiglu_grad(dy, D, wdT, D, T, D, F, g, u, F, dg, du, ldd, st);
+  const void* dys[1] = {dy}; const void* ws[1] = {wdT}; const int64_t ns[1] = {D};
+  TRY(gemm_dgrad_t(1, dys, ws, ns, 0, T, F, dg, ldd, st));
+  return launch_swiglu_bwd_rows(g, u, dg, T, F, F, ldd, dg, du, st);
+}
 // dw[N,K] (+)= dy[T,N]^T x[T,K]; lddy, ldx: leading dimensions of dy and x
 static GemmArgs wgrad_args(const void* dy, int64_t lddy, const void* x, int64_t ldx, int64_t T, int64_t N, int64_t K,
                            void* dw, int accumulate) {
@@ -257,11 +268,7 @@ int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* 
   TRY(launch_transpose(w->wk, k.wkT, KD, D, KD, st));
   TRY(launch_transpose(w->wv, k.wvT, KD, D, KD, st));
   // y = y1 + a Wd^T
-  {
-    const void* dys[1] = {dy}; const void* ws[1] = {k.wdT}; const int64_t ns[1] = {D};
-    TRY(gemm_dgrad_t(1, dys, ws, ns, 0, T, F, k.da_dg, Fp, st));
-  }
-  TRY(launch_swiglu_bwd_rows(s.g, s.u, k.da_dg, T, F, F, Fp, k.da_dg, k.du, st));
+  TRY(down_dgrad_swiglu(dy, k.wdT, T, D, F, s.g, s.u, k.da_dg, k.du, Fp, st));
   {
     const void* dys[2] = {k.da_dg, k.du}; const void* ws[2] = {k.wgT, k.wuT}; const int64_t ns[2] = {F, F};
     TRY(gemm_dgrad_t(2, dys, ws, ns, Fp, T, D, k.dh2, D, st));
@@ -372,6 +379,24 @@ int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int
   }
   if (dw) TRY(gemm_wgrad(dy, x, T, N, K, dw, accumulate_dw ? 1 : 0, st));
   return DLAYER_OK;
+}
+
+size_t linear_swiglu_backward_workspace_bytes(int64_t T, int64_t D, int64_t F) {
+  return T > 0 && D > 0 && F > 0 ? (size_t)D * F * 2 : 0;   // W_down^T
+}
+
+int linear_swiglu_backward(const void* dy, const void* w_down, const void* g, const void* u, int64_t T, int64_t D,
+                           int64_t F, void* dg, void* du, void* workspace, void* stream) {
+  REQUIRE(T > 0 && D > 0 && F > 0 && T % 64 == 0 && D % 64 == 0 && F % 64 == 0,
+          "linear_swiglu_backward: T, D and F must be multiples of 64");
+  REQUIRE(T * D * 2 < ((int64_t)1 << 32) && D * F * 2 < ((int64_t)1 << 32) && T * F * 2 < ((int64_t)1 << 32),
+          "linear_swiglu_backward: an operand reaches 4 GiB");
+  REQUIRE_PTR(dy); REQUIRE_PTR(w_down); REQUIRE_PTR(g); REQUIRE_PTR(u); REQUIRE_PTR(dg); REQUIRE_PTR(du);
+  REQUIRE_PTR(workspace);
+  TRY(check_device());
+  hipStream_t st = (hipStream_t)stream;
+  TRY(launch_transpose(w_down, workspace, D, F, D, st));
+  return down_dgrad_swiglu(dy, workspace, T, D, F, g, u, dg, du, F, st);
 }
 
 int linear_wgrad_group(int32_t n, const void* const* dy, const void* const* x, const int64_t* N, const int64_t* K,

@@ -62,6 +62,9 @@ struct GemmKArgs {
   const bf16_t* b2;
   bf16_t *c2, *c3;
   int64_t ldc3;
+  // activation-gradient epilogue only (see EPI_SWIGLU_GRAD)
+  const bf16_t *e1, *e2;
+  int64_t lde;
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
@@ -303,11 +306,16 @@ struct GemmGroupKArgs {
 // problem by comparing against each index in turn): a run-time index into the argument block would
 // make the compiler copy the whole block to scratch memory and read it back through vector loads.
 //
-// SWIGLU: the gated pair of the MLP in one pass.  B interleaves the rows of two weight matrices
+// EPI_SWIGLU: the gated pair of the MLP in one pass.  B interleaves the rows of two weight matrices
 // (LoadCursor PAIR) so that every wave holds g = x Wg^T and u = x Wu^T for the same 32 columns; the
 // epilogue stores g to c, u to c2 and silu(g) * u, taken from the ROUNDED g and u like the separate
 // activation kernel would, to c3.  M x N is the interleaved product: N = twice the columns of g.
-template <bool GROUPED, int BM, int BN, int WM, int WN, bool AK, bool BKM, bool SWIGLU = false>
+//
+// EPI_SWIGLU_GRAD: the product is da, the gradient arriving at a = silu(g) * u; the epilogue reads the
+// g and u tiles (e1, e2, leading dimension lde) and stores dg to c and du to c2 instead of da,
+// again from the rounded da like the separate kernel.
+enum { EPI_PLAIN = 0, EPI_SWIGLU = 1, EPI_SWIGLU_GRAD = 2 };
+template <bool GROUPED, int BM, int BN, int WM, int WN, bool AK, bool BKM, int EPI = EPI_PLAIN>
 __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const GemmKArgs& one) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
@@ -341,8 +349,9 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
   // What the epilogue needs of a tile's problem, by value (the next tile's cursor is opened before the
   // current tile's epilogue runs).
   struct Tile { int m0, n0, total, M, N, accumulate; bf16_t* c; const bf16_t* r; int64_t ldc; };
+  constexpr bool SWIGLU = EPI == EPI_SWIGLU;
   LoadCursor<BM, BN, NL, AK, BKM, SWIGLU> cur;
-  static_assert(!SWIGLU || (!GROUPED && TN == 64 && MI == 16), "gated pair: one 64-column strip per wave");
+  static_assert(EPI == EPI_PLAIN || (!GROUPED && TN == 64 && MI == 16), "fused epilogues: one 64-column strip per wave");
 
   // tile id -> tile origin, and the load cursor opened on the tile's first K-segment.  The tile
   // sequence of a problem runs in bands of 8 tile-rows, so that the ~32 consecutive tiles an XCD holds
@@ -546,7 +555,81 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
       const int n = i * MI + (MI == 32 ? g * 8 + lq * 4 : lq * 4);
       return row * 128 + ((((n >> 3) ^ ((row >> 1) & 7)) << 4) | ((n & 4) << 1));
     };
-    if constexpr (SWIGLU) {
+    if constexpr (EPI == EPI_SWIGLU_GRAD) {
+      // In steps of one MFMA block row (MI rows x 64 columns per wave), which keeps the registers the
+      // step needs next to the accumulators few: a whole row quarter at a time made the compiler
+      // spill values the main loop uses.
+      const int nbase = n0 + wave_n * TN;
+      constexpr int NT = MI / 8;
+      // block rows whose g and u are in flight ahead of the one being worked on.  Two or three ahead
+      // measure the same (three spills registers of the main loop): all workgroups reach their
+      // epilogues together, and what the reads then wait for is HBM bandwidth, not latency.
+      constexpr int PF = 1;
+      bf16x8 gv[PF + 1][NT], uv[PF + 1][NT];
+      // g and u of block row s, 16 bytes per lane along rows (the layout of the drain below)
+      auto fetch = [&](int s, bf16x8 (&g8)[NT], bf16x8 (&u8)[NT]) {
+        const int mbase = m0 + wave_m * TM + s * MI;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const int row = t * 8 + rrow;
+          const int m = mbase + row;
+          const int n = nbase + ((rpc ^ ((row >> 1) & 7)) << 3);
+          const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+          g8[t] = zero;
+          u8[t] = zero;
+          if (m < p.M && n < p.N) {
+            g8[t] = *reinterpret_cast<const bf16x8*>(one.e1 + (int64_t)m * one.lde + n);
+            u8[t] = *reinterpret_cast<const bf16x8*>(one.e2 + (int64_t)m * one.lde + n);
+          }
+        }
+      };
+      // rows -> accumulator layout through the staging area
+      auto to_acc_layout = [&](const bf16x8 (&v8)[NT], bf16x4 (&q)[TPB]) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) *reinterpret_cast<bf16x8*>(stg + (t * 8 + rrow) * 128 + (rpc << 4)) = v8[t];
+#pragma unroll
+        for (int i = 0; i < TPB; ++i) q[i] = *reinterpret_cast<const bf16x4*>(stg + stg_off(0, i, 0));
+      };
+      auto drain = [&](int s, const bf16x4 (&q)[TPB], bf16_t* dst) {
+#pragma unroll
+        for (int i = 0; i < TPB; ++i) *reinterpret_cast<bf16x4*>(stg + stg_off(0, i, 0)) = q[i];
+        const int mbase = m0 + wave_m * TM + s * MI;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const int row = t * 8 + rrow;
+          const int m = mbase + row;
+          const int n = nbase + ((rpc ^ ((row >> 1) & 7)) << 3);
+          const bf16x8 v = *reinterpret_cast<const bf16x8*>(stg + row * 128 + (rpc << 4));
+          if (m < p.M && n < p.N) *reinterpret_cast<bf16x8*>(dst + (int64_t)m * p.ldc + n) = v;
+        }
+      };
+      static_for<0, PF>([&](auto s_c) {
+        constexpr int s = decltype(s_c)::value;
+        fetch(s, gv[s], uv[s]);
+      });
+      static_for<0, FM>([&](auto s_c) {
+        constexpr int s = decltype(s_c)::value;
+        bf16x4 gq[TPB], uq[TPB];
+        to_acc_layout(gv[s % (PF + 1)], gq);
+        to_acc_layout(uv[s % (PF + 1)], uq);
+        // each fetch is issued before this row's stores, so waiting for it does not wait for the stores
+        if constexpr (s + PF < FM) fetch(s + PF, gv[(s + PF) % (PF + 1)], uv[(s + PF) % (PF + 1)]);
+#pragma unroll
+        for (int i = 0; i < TPB; ++i)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float z = (float)gq[i][e], d = (float)(bf16_t)acc[i][s][e];
+            const float sg = 1.0f / (1.0f + __expf(-z));
+            gq[i][e] = (bf16_t)(d * (float)uq[i][e] * sg * (1.0f + z * (1.0f - sg)));
+            uq[i][e] = (bf16_t)(d * z * sg);
+          }
+        if (s == 0 && more) {
+          if (tl.total >= 2) wait_vmcnt<LPW>(); else wait_vmcnt<0>();
+        }
+        drain(s, gq, p.c);
+        drain(s, uq, one.c2);
+      });
+    } else if constexpr (SWIGLU) {
       // staged columns 0..31 are g, 32..63 are u, both for columns nh .. nh+31 of their matrices
       const int nh = n0 / 2 + wave_n * 32, NH = p.N / 2;
 #pragma unroll
@@ -662,9 +745,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmKArgs p) {
   gemm_persistent<false, BM, BN, WM, WN, AK, BKM>(GemmGroupKArgs{}, p);
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_swiglu_kernel(const GemmKArgs p) {
-  gemm_persistent<false, BM, BN, WM, WN, true, true, true>(GemmGroupKArgs{}, p);
+  gemm_persistent<false, BM, BN, WM, WN, true, true, EPI>(GemmGroupKArgs{}, p);
 }
 
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
@@ -779,13 +862,33 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
 bool gemm_swiglu_applies(int64_t T, int64_t F) {
   return F % 8 == 0 && ((T + 255) / 256) * ((2 * F + 255) / 256) >= 192;
 }
+bool gemm_swiglu_grad_applies(int64_t T, int64_t F) {
+  return F % 8 == 0 && ((T + 255) / 256) * ((F + 255) / 256) >= 192;
+}
+
+template <int EPI>
+static int launch_fused(GemmKArgs k, const char* what, hipStream_t st) {
+  constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
+  k.nseg = 1;
+  k.tiles_m = (k.M + BM - 1) / BM;
+  k.tiles_n = (k.N + BN - 1) / BN;
+  const dim3 grid((unsigned)persistent_grid(k.tiles_m * k.tiles_n)), block(WM * WN * 64);
+  const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
+  auto kern = gemm_swiglu_kernel<BM, BN, WM, WN, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return fail(-3, "gemm: cannot reserve %zu B of LDS: %s", lds, hipGetErrorString(e));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, block, lds, st, k);
+  return check_launch(what);
+}
 
 int launch_gemm_swiglu(const void* x, int64_t ldx, const void* wg, const void* wu, int64_t ldw, int64_t T, int64_t K,
                        int64_t F, void* g, void* u, int64_t ldgu, void* a, int64_t lda, hipStream_t st) {
   if (!gemm_swiglu_applies(T, F)) return fail(-1, "gemm swiglu: shape T=%lld F=%lld not served by the fused kernel", (long long)T, (long long)F);
-  constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
   GemmKArgs k{};
-  k.nseg = 1;
   k.a[0] = (const bf16_t*)x;
   k.b[0] = (const bf16_t*)wg;
   k.b2 = (const bf16_t*)wu;
@@ -799,19 +902,28 @@ int launch_gemm_swiglu(const void* x, int64_t ldx, const void* wg, const void* w
   k.ldc = ldgu;
   k.c3 = (bf16_t*)a;
   k.ldc3 = lda;
-  k.tiles_m = (k.M + BM - 1) / BM;
-  k.tiles_n = (k.N + BN - 1) / BN;
-  const dim3 grid((unsigned)persistent_grid(k.tiles_m * k.tiles_n)), block(WM * WN * 64);
-  const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
-  auto kern = gemm_swiglu_kernel<BM, BN, WM, WN>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return fail(-3, "gemm: cannot reserve %zu B of LDS: %s", lds, hipGetErrorString(e));
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(kern, grid, block, lds, st, k);
-  return check_launch("gemm swiglu");
+  return launch_fused<EPI_SWIGLU>(k, "gemm swiglu", st);
+}
+
+int launch_gemm_swiglu_grad(const void* dy, int64_t lddy, const void* wt, int64_t ldw, int64_t T, int64_t K, int64_t F,
+                            const void* g, const void* u, int64_t ldgu, void* dg, void* du, int64_t ldd,
+                            hipStream_t st) {
+  if (!gemm_swiglu_grad_applies(T, F)) return fail(-1, "gemm swiglu grad: shape T=%lld F=%lld not served by the fused kernel", (long long)T, (long long)F);
+  GemmKArgs k{};
+  k.a[0] = (const bf16_t*)dy;
+  k.b[0] = (const bf16_t*)wt;
+  k.lda[0] = lddy;
+  k.ldb[0] = ldw;
+  k.K[0] = (int)K;
+  k.M = (int)T;
+  k.N = (int)F;
+  k.c = (bf16_t*)dg;
+  k.c2 = (bf16_t*)du;
+  k.ldc = ldd;
+  k.e1 = (const bf16_t*)g;
+  k.e2 = (const bf16_t*)u;
+  k.lde = ldgu;
+  return launch_fused<EPI_SWIGLU_GRAD>(k, "gemm swiglu grad", st);
 }
 
 int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st) {

@@ -63,6 +63,12 @@ int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st);
 bool gemm_swiglu_applies(int64_t T, int64_t F);
 int launch_gemm_swiglu(const void* x, int64_t ldx, const void* wg, const void* wu, int64_t ldw, int64_t T, int64_t K,
                        int64_t F, void* g, void* u, int64_t ldgu, void* a, int64_t lda, hipStream_t st);
+// da = dy W^T for dy [T, K] (lddy) and wt = W [F, K] (ldw), then (dg, du) = gradient of silu(g) * u for
+// the rounded da, without da ever being stored.  g, u with ldgu; dg, du with ldd.
+bool gemm_swiglu_grad_applies(int64_t T, int64_t F);
+int launch_gemm_swiglu_grad(const void* dy, int64_t lddy, const void* wt, int64_t ldw, int64_t T, int64_t K, int64_t F,
+                            const void* g, const void* u, int64_t ldgu, void* dg, void* du, int64_t ldd,
+                            hipStream_t st);
 
 // ---- attention.hip
 int launch_attention_fwd(const void* q, const void* k, const void* v, int64_t B, int64_t S,

@@ -185,6 +185,34 @@ def test_linear_swiglu_forward(K, T, Kd, F):
         assert torch.equal(p.view(torch.int16), q.view(torch.int16)), f"{name}: fused and separate launches differ"
 
 
+@pytest.mark.parametrize("T,D,F", [
+    (256, 128, 512),        # small: product, then the activation-gradient kernel
+    (2048, 256, 6144),      # 192 tiles of 256 x 256: the fused kernel
+    (1984, 192, 6208),      # fused, ragged in T and F
+    (2304, 128, 8256),      # fused, more tiles than CUs, ragged F
+])
+def test_linear_swiglu_backward(K, T, D, F):
+    """da = dy W_down and the SwiGLU gradient in one call: against the oracle, and bit for bit against
+    the input-gradient product and the activation gradient launched separately."""
+    rng = np.random.default_rng(T + F + 3)
+    dyb, wb = _rand_bits(rng, (T, D)), _rand_bits(rng, (D, F), 0.1)
+    gb, ub = _rand_bits(rng, (T, F)), _rand_bits(rng, (T, F))
+    dy, w, g, u = map(si.bf16_bits_to_f64, (dyb, wb, gb, ub))
+    dyd, wd, gd, ud = map(dev_bf16, (dyb, wb, gb, ub))
+    dg, du = (torch.full((T, F), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(2))
+    K.linear_swiglu_backward(dyd, wd, gd, ud, T, D, F, dg, du, _ws(K.linear_swiglu_backward_workspace_bytes(T, D, F)))
+    dg_ref, du_ref = odl.swiglu_bwd(g, u, dy @ w)
+    assert_close(dg, dg_ref, "dg", rel_tol=1.5e-2)
+    assert_close(du, du_ref, "du", rel_tol=1.5e-2)
+    da = torch.full((T, F), float("nan"), dtype=torch.bfloat16, device="cuda")
+    x_unused = torch.zeros((T, F), dtype=torch.bfloat16, device="cuda")
+    K.linear_backward(x_unused, wd, dyd, T, F, D, da, None, 0, _ws(K.linear_backward_workspace_bytes(T, F, D)))
+    dg2, du2 = torch.empty_like(dg), torch.empty_like(du)
+    K.swiglu_backward(gd, ud, da, T * F, dg2, du2)
+    for name, p, q in (("dg", dg, dg2), ("du", du, du2)):
+        assert torch.equal(p.view(torch.int16), q.view(torch.int16)), f"{name}: fused and separate launches differ"
+
+
 @pytest.mark.parametrize("Kd,N,res", [(4096, 14336, False), (14336, 4096, True)])
 def test_linear_full_size_sampled(K, Kd, N, res):
     """The two widest projections of the 8B-shaped layer at their full size (T = 16384), as the
