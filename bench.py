@@ -22,12 +22,12 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/s)
 
-# HBM bytes per launch of the dominant kernel (mean over the seven forward-projection launches of the
-# 8B-shaped layer), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain 1 GiB copy in the same
+# HBM bytes per launch of the dominant kernel (mean over the replayed launches of the seven projection
+# shapes of the 8B-shaped layer), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain 1 GiB copy in the same
 # run (factors 2.0 and 1.0; profiles/layer_8b_hbm_traffic.txt).  Only valid for the GEMM source the
 # counters were taken on: reported as null when gemm.hip has changed since.
-GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "01fbe9eb9df0d7f66bab715373a78fbd826279cbed12460867ddf7433685e412",
-                "fetch_bytes": 1.534e+09, "write_bytes": 2.013e+08}
+GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "98ea69748a81fea3d3103702211442d7ff70edc968ee787bb053259039248c5f",
+                "fetch_bytes": 1.496e+09, "write_bytes": 2.013e+08}
 
 
 def _gemm_traffic(config_name):
@@ -144,9 +144,11 @@ def main():
     fwd_ms = timed(lambda: K.dlayer_forward(cfg, x, w, y, saved, ws), n_sub)
     bwd_ms = timed(lambda: K.dlayer_backward(cfg, x, w, dy, saved, dx, dw, 0, ws), n_sub)
 
-    # Dominant kernel: the k-major x k-major bf16 MFMA GEMM (all seven forward projections of the
-    # step run on it).  Replay exactly those seven launches, one event pair per launch on the launch
-    # stream, and compare algorithmic FLOPs with the summed durations.
+    # Dominant kernel: the k-major x k-major bf16 MFMA GEMM.  The q, k, v, o and down projections and
+    # every input-gradient product of the step run on it, the gate/up pair and the down-projection
+    # input gradient on variants of it with the SwiGLU in the epilogue.  Launch it at the layer's
+    # seven projection shapes, one event pair per launch on the launch stream, and compare algorithmic
+    # FLOPs with the summed durations.
     T, D, F = cfg.tokens, cfg.d_model, cfg.d_ff
     QD, KD = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
     acts = {D: x.view(T, D), QD: torch.empty(T, QD, dtype=torch.bfloat16, device="cuda").normal_(),
@@ -168,7 +170,7 @@ def main():
     torch.cuda.synchronize()
     total_ms = sum(a.elapsed_time(b) for a, b in dur_ms)
     achieved = gemm_flops / (total_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_kernel<256,256,2,4,k-major,k-major> (7 projection launches/step)",
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel<256,256,2,4,k-major,k-major> (the layer's 7 projection shapes)",
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                 "avg_launch_ms": total_ms / len(dur_ms), "launches_timed": len(dur_ms),
                 "traffic": _gemm_traffic(args.config), "traffic_unit": "HBM bytes per launch (fetched + written)",
