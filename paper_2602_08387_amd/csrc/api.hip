@@ -146,8 +146,7 @@ static int gemm_nt(const void* x, int64_t ldx, const void* w, const void* res, i
   g.a_kmajor = true; g.b_kmajor = true;
   return launch_gemm(g, st);
 }
-// dx[T,K] = sum_s dy_s[T,N_s] WT_s[K,N_s]^T with the transposed weights WT_s = W_s^T; ld: leading
-// dimension of every dy_s and WT_s, lddx: that of dx
+
 // g = x Wg^T, u = x Wu^T, a = silu(g) * u (a with leading dimension lda): one fused launch when the
 // problem fills the chip with 256 x 256 tiles, otherwise two products and the activation kernel.
 // Both routes give the same bits (the fused epilogue applies the activation to the rounded g, u).
@@ -159,6 +158,8 @@ static int gate_up_swiglu(const void* x, const void* wg, const void* wu, int64_t
   return launch_swiglu_fwd_rows(g, u, T, F, F, a, lda, st);
 }
 
+// dx[T,K] = sum_s dy_s[T,N_s] WT_s[K,N_s]^T with the transposed weights WT_s = W_s^T; ld: leading
+// dimension of every dy_s and WT_s, lddx: that of dx
 static int gemm_dgrad_t(int nseg, const void* const* dy, const void* const* wt, const int64_t* Ns, int64_t ld,
                         int64_t T, int64_t K, void* dx, int64_t lddx, hipStream_t st) {
   GemmArgs g{};
@@ -179,6 +180,7 @@ static int down_dgrad_swiglu(const void* dy, const void* wdT, int64_t T, int64_t
   TRY(gemm_dgrad_t(1, dys, ws, ns, 0, T, F, dg, ldd, st));
   return launch_swiglu_bwd_rows(g, u, dg, T, F, F, ldd, dg, du, st);
 }
+
 // dw[N,K] (+)= dy[T,N]^T x[T,K]; lddy, ldx: leading dimensions of dy and x
 static GemmArgs wgrad_args(const void* dy, int64_t lddy, const void* x, int64_t ldx, int64_t T, int64_t N, int64_t K,
                            void* dw, int accumulate) {
