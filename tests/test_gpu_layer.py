@@ -112,6 +112,36 @@ def test_layer_is_causal_and_deterministic(K):
     assert not torch.equal(y1[:, t + 1:].view(torch.int16), g2.y[:, t + 1:].view(torch.int16))
 
 
+@pytest.mark.parametrize("name", ["tiny", "small"])
+def test_layer_replays_from_a_hip_graph(K, name):
+    """The calls only enqueue kernels (no allocation, memset or synchronisation), so a forward +
+    backward can be captured once and replayed: three replays on fresh inputs, each with eager work
+    and synchronisations in between, must reproduce the eager results bit for bit."""
+    cfg = si.CONFIGS[name]
+    inps = [si.make_layer_inputs(cfg, seed=s) for s in (3, 4, 5)]
+    g = GpuLayer(K, cfg, inps[0])
+    g.forward(); g.backward()              # first call outside capture: one-time kernel attributes
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g.forward(); g.backward()
+    names = ("y", "dx") + tuple(si.WEIGHT_NAMES)
+    outs = lambda o: [o.y, o.dx] + [o.dw[n] for n in si.WEIGHT_NAMES]
+    for inp in inps:
+        e = GpuLayer(K, cfg, inp)           # eager reference on buffers of its own
+        e.forward(); e.backward()
+        torch.cuda.synchronize()
+        g.x.copy_(e.x); g.dy.copy_(e.dy)
+        for n in si.WEIGHT_NAMES:
+            g.w[n].copy_(e.w[n])
+        for t in outs(g):
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, a, b in zip(names, outs(g), outs(e)):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"{name}: {n} differs between replay and eager"
+
+
 # At D = 4096, F = 14336 the element-wise metric (max over ~1e6 outputs of |err| / max(|ref|, rms))
 # of ANY pipeline that rounds MFMA operands to bf16 exceeds 2e-2: rounding only h1, q, k, v, o, h2, a
 # and y (each needed as an MFMA operand or as the output) in an otherwise exact fp64 evaluation gives
