@@ -755,8 +755,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_group_kernel(const GemmGroup
   gemm_persistent<true, BM, BN, WM, WN, AK, BKM>(g, g.prob[0]);
 }
 
-// One workgroup per CU (the LDS ring allows no second one), fewer if there are fewer tiles.
-static int persistent_grid(int ntiles) {
+// As many workgroups as the LDS lets a CU hold at once (one for the 256 x 256 tile's 160 KB, two for
+// the 128 x 128 tile's 72 KB, which then also gives every SIMD a second wave), fewer if there are fewer
+// tiles.
+static int persistent_grid(int ntiles, size_t lds) {
   static int cus = 0;
   if (cus == 0) {
     int dev = 0;
@@ -764,7 +766,8 @@ static int persistent_grid(int ntiles) {
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return ntiles;
     cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
-  return ntiles < cus ? ntiles : cus;
+  const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
+  return ntiles < cus * per_cu ? ntiles : cus * per_cu;
 }
 
 template <int BM, int BN>
@@ -783,8 +786,8 @@ static int launch_group_cfg(const GemmKArgs* ks, int n, bool ak, bool bk, hipStr
     g.prob[i].tiles_n = (ks[i].N + BN - 1) / BN;
     g.tile_start[i + 1] = g.tile_start[i] + g.prob[i].tiles_m * g.prob[i].tiles_n;
   }
-  const dim3 grid((unsigned)persistent_grid(g.tile_start[n])), block(WM * WN * 64);
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
+  const dim3 grid((unsigned)persistent_grid(g.tile_start[n], lds)), block(WM * WN * 64);
 #define GEMM_GROUP_LAUNCH(AK_, BK_)                                                              \
   do {                                                                                           \
     auto kern = gemm_group_kernel<BM, BN, WM, WN, AK_, BK_>;                                     \
@@ -809,8 +812,8 @@ static int launch_cfg(const GemmKArgs& k, bool ak, bool bk, hipStream_t st) {
   GemmKArgs a = k;
   a.tiles_m = (k.M + BM - 1) / BM;
   a.tiles_n = (k.N + BN - 1) / BN;
-  const dim3 grid((unsigned)persistent_grid(a.tiles_m * a.tiles_n)), block(WM * WN * 64);
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
+  const dim3 grid((unsigned)persistent_grid(a.tiles_m * a.tiles_n, lds)), block(WM * WN * 64);
 #define GEMM_LAUNCH(AK_, BK_)                                                                    \
   do {                                                                                           \
     auto kern = gemm_kernel<BM, BN, WM, WN, AK_, BK_>;                                           \
@@ -872,8 +875,8 @@ static int launch_fused(GemmKArgs k, const char* what, hipStream_t st) {
   k.nseg = 1;
   k.tiles_m = (k.M + BM - 1) / BM;
   k.tiles_n = (k.N + BN - 1) / BN;
-  const dim3 grid((unsigned)persistent_grid(k.tiles_m * k.tiles_n)), block(WM * WN * 64);
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
+  const dim3 grid((unsigned)persistent_grid(k.tiles_m * k.tiles_n, lds)), block(WM * WN * 64);
   auto kern = gemm_swiglu_kernel<BM, BN, WM, WN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
