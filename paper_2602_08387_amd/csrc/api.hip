@@ -137,14 +137,18 @@ static Work carve_work(const dlayer_cfg* c, void* p) {
 }
 
 // y[T,N] = x[T,K] W[N,K]^T (+ residual); ldx: leading dimension of x
-static int gemm_nt(const void* x, int64_t ldx, const void* w, const void* res, int64_t T, int64_t K, int64_t N, void* y,
-                   hipStream_t st) {
+static GemmArgs nt_args(const void* x, int64_t ldx, const void* w, const void* res, int64_t T, int64_t K, int64_t N,
+                        void* y) {
   GemmArgs g{};
   g.nseg = 1;
   g.seg[0] = {x, w, ldx, K, (int)K};
   g.M = (int)T; g.N = (int)N; g.c = y; g.ldc = N; g.r = res; g.accumulate = 0;
   g.a_kmajor = true; g.b_kmajor = true;
-  return launch_gemm(g, st);
+  return g;
+}
+static int gemm_nt(const void* x, int64_t ldx, const void* w, const void* res, int64_t T, int64_t K, int64_t N, void* y,
+                   hipStream_t st) {
+  return launch_gemm(nt_args(x, ldx, w, res, T, K, N, y), st);
 }
 
 // g = x Wg^T, u = x Wu^T, a = silu(g) * u (a with leading dimension lda): one fused launch when the
@@ -229,11 +233,14 @@ int dlayer_forward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w
   const int64_t Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, dh = cfg->head_dim, QD = Hq * dh, KD = Hkv * dh;
   Saved s = carve_saved(cfg, saved);
   TRY(launch_rmsnorm_fwd(x, w->g_attn, T, D, cfg->rms_eps, s.h1, s.rstd1, st));
-  TRY(gemm_nt(s.h1, D, w->wq, nullptr, T, D, QD, s.q, st));
-  TRY(gemm_nt(s.h1, D, w->wk, nullptr, T, D, KD, s.k, st));
-  TRY(gemm_nt(s.h1, D, w->wv, nullptr, T, D, KD, s.v, st));
-  TRY(launch_rope(s.q, B, S, Hq, dh, cfg->rope_base, cfg->rope_layout, 0, st));
-  TRY(launch_rope(s.k, B, S, Hkv, dh, cfg->rope_base, cfg->rope_layout, 0, st));
+  {
+    // q, k and v in one launch: their tile sequences run end to end (k and v alone do not fill the chip
+    // for small layers)
+    const GemmArgs qkv[3] = {nt_args(s.h1, D, w->wq, nullptr, T, D, QD, s.q), nt_args(s.h1, D, w->wk, nullptr, T, D, KD, s.k),
+                             nt_args(s.h1, D, w->wv, nullptr, T, D, KD, s.v)};
+    TRY(launch_gemm_group(qkv, 3, st));
+  }
+  TRY(launch_rope_pair(s.q, s.k, B, S, Hq, Hkv, dh, cfg->rope_base, cfg->rope_layout, 0, st));
   TRY(launch_attention_fwd(s.q, s.k, s.v, B, S, Hq, Hkv, dh, s.o, s.lse, st));
   TRY(gemm_nt(s.o, QD, w->wo, x, T, QD, D, s.y1, st));
   TRY(launch_rmsnorm_fwd(s.y1, w->g_mlp, T, D, cfg->rms_eps, s.h2, s.rstd2, st));
@@ -262,13 +269,12 @@ int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* 
   Saved s = carve_saved(cfg, const_cast<void*>(saved));
   Work k = carve_work(cfg, workspace);
   const int64_t Fp = padded_ff(cfg);
-  TRY(launch_transpose(w->w_down, k.wdT, D, F, D, st));
-  TRY(launch_transpose(w->w_gate, k.wgT, F, D, Fp, st));
-  TRY(launch_transpose(w->w_up, k.wuT, F, D, Fp, st));
-  TRY(launch_transpose(w->wo, k.woT, D, QD, D, st));
-  TRY(launch_transpose(w->wq, k.wqT, QD, D, QD, st));
-  TRY(launch_transpose(w->wk, k.wkT, KD, D, KD, st));
-  TRY(launch_transpose(w->wv, k.wvT, KD, D, KD, st));
+  {
+    const TransposeJob jobs[7] = {{w->w_down, k.wdT, D, F, D},  {w->w_gate, k.wgT, F, D, Fp}, {w->w_up, k.wuT, F, D, Fp},
+                                  {w->wo, k.woT, D, QD, D},     {w->wq, k.wqT, QD, D, QD},    {w->wk, k.wkT, KD, D, KD},
+                                  {w->wv, k.wvT, KD, D, KD}};
+    TRY(launch_transpose_group(jobs, 7, st));
+  }
   // y = y1 + a Wd^T
   TRY(down_dgrad_swiglu(dy, k.wdT, T, D, F, s.g, s.u, k.da_dg, k.du, Fp, st));
   {
@@ -282,8 +288,7 @@ int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* 
     TRY(gemm_dgrad_t(1, dys, ws, ns, 0, T, QD, k.d_o, QD, st));
   }
   TRY(launch_attention_bwd(s.q, s.k, s.v, s.o, k.d_o, s.lse, B, S, Hq, Hkv, dh, k.dq, k.dk, k.dv, k.attn_ws, st));
-  TRY(launch_rope(k.dq, B, S, Hq, dh, cfg->rope_base, cfg->rope_layout, 1, st));
-  TRY(launch_rope(k.dk, B, S, Hkv, dh, cfg->rope_base, cfg->rope_layout, 1, st));
+  TRY(launch_rope_pair(k.dq, k.dk, B, S, Hq, Hkv, dh, cfg->rope_base, cfg->rope_layout, 1, st));
   {
     const void* dys[3] = {k.dq, k.dk, k.dv}; const void* ws[3] = {k.wqT, k.wkT, k.wvT};
     const int64_t ns[3] = {QD, KD, KD};

@@ -155,10 +155,19 @@ __global__ __launch_bounds__(256) void colsum_partials_kernel(const float* __res
   __shared__ float red[8][33];
   const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
   const int c = blockIdx.x * 32 + cl;
-  float s = 0.f;
-  if (c < D)
-    for (int r = rg; r < nrows; r += 8) s += partial[(int64_t)r * D + c];
-  red[rg][cl] = s;
+  // four loads in flight per thread: the loop is latency-bound otherwise (20 us for 512 rows)
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (c < D) {
+    int r = rg;
+    for (; r + 24 < nrows; r += 32) {
+      s0 += partial[(int64_t)r * D + c];
+      s1 += partial[(int64_t)(r + 8) * D + c];
+      s2 += partial[(int64_t)(r + 16) * D + c];
+      s3 += partial[(int64_t)(r + 24) * D + c];
+    }
+    for (; r < nrows; r += 8) s0 += partial[(int64_t)r * D + c];
+  }
+  red[rg][cl] = (s0 + s1) + (s2 + s3);
   __syncthreads();
   if (rg == 0 && c < D) {
     float t = 0.f;
@@ -215,21 +224,10 @@ int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, cons
 // range reduction is not accurate enough), park them in LDS as fp32, then every thread rotates
 // pairs of all heads of that token.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void rope_kernel(bf16_t* z, int seq, int n_heads, int head_dim,
-                                                   double log2_base, int layout, int inverse) {
-  __shared__ float cs[64], sn[64];
-  const int64_t tok = blockIdx.x;
-  const int p = (int)(tok % seq);
+// rotates all heads of one token row zt ([n_heads, head_dim]) with the angles parked in cs / sn
+__device__ __forceinline__ void rope_rotate_row(bf16_t* zt, const float* cs, const float* sn, int n_heads,
+                                                int head_dim, int layout) {
   const int half = head_dim >> 1;
-  if ((int)threadIdx.x < half) {
-    const double theta = exp2(-2.0 * (double)threadIdx.x / (double)head_dim * log2_base);
-    double s, c;
-    sincos((double)p * theta, &s, &c);
-    cs[threadIdx.x] = (float)c;
-    sn[threadIdx.x] = inverse ? -(float)s : (float)s;
-  }
-  __syncthreads();
-  bf16_t* zt = z + tok * (int64_t)n_heads * head_dim;
   if (layout == 0) {
     // pairs (i, i + half): handle 8 consecutive i per thread
     const int groups = half >> 3;  // per head
@@ -265,11 +263,38 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* z, int seq, int n_hea
   }
 }
 
+// z2 (n_heads2 heads per token) is an optional second tensor rotated by the same angles: q and k of
+// a layer in one launch, with the fp64 trigonometry done once.
+__global__ __launch_bounds__(256) void rope_kernel(bf16_t* z, bf16_t* z2, int seq, int n_heads, int n_heads2,
+                                                   int head_dim, double log2_base, int layout, int inverse) {
+  __shared__ float cs[64], sn[64];
+  const int64_t tok = blockIdx.x;
+  const int p = (int)(tok % seq);
+  const int half = head_dim >> 1;
+  if ((int)threadIdx.x < half) {
+    const double theta = exp2(-2.0 * (double)threadIdx.x / (double)head_dim * log2_base);
+    double s, c;
+    sincos((double)p * theta, &s, &c);
+    cs[threadIdx.x] = (float)c;
+    sn[threadIdx.x] = inverse ? -(float)s : (float)s;
+  }
+  __syncthreads();
+  rope_rotate_row(z + tok * (int64_t)n_heads * head_dim, cs, sn, n_heads, head_dim, layout);
+  if (z2) rope_rotate_row(z2 + tok * (int64_t)n_heads2 * head_dim, cs, sn, n_heads2, head_dim, layout);
+}
+
 int launch_rope(void* z, int64_t batch, int64_t seq, int64_t n_heads, int64_t head_dim,
                 float base, int layout, int inverse, hipStream_t st) {
-  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)(batch * seq)), dim3(256), 0, st, (bf16_t*)z,
-                     (int)seq, (int)n_heads, (int)head_dim, log2((double)base), layout, inverse);
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)(batch * seq)), dim3(256), 0, st, (bf16_t*)z, (bf16_t*)nullptr,
+                     (int)seq, (int)n_heads, 0, (int)head_dim, log2((double)base), layout, inverse);
   return check_launch("rope_apply");
+}
+
+int launch_rope_pair(void* q, void* k, int64_t batch, int64_t seq, int64_t n_q_heads, int64_t n_kv_heads,
+                     int64_t head_dim, float base, int layout, int inverse, hipStream_t st) {
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)(batch * seq)), dim3(256), 0, st, (bf16_t*)q, (bf16_t*)k, (int)seq,
+                     (int)n_q_heads, (int)n_kv_heads, (int)head_dim, log2((double)base), layout, inverse);
+  return check_launch("rope_apply(q, k)");
 }
 
 // ------------------------------------------------------------------------------------------
@@ -420,11 +445,9 @@ int launch_swiglu_bwd_rows(const void* g, const void* u, const void* da, int64_t
 // bf16 transpose: out[c][r] = in[r][c], 64x64 tiles through LDS (16-byte global accesses on
 // both sides).  R and C are multiples of 64.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void transpose_kernel(const bf16_t* __restrict__ in,
-                                                        bf16_t* __restrict__ out, int64_t R,
-                                                        int64_t C, int64_t ld_out) {
+__device__ __forceinline__ void transpose_tile(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int64_t C,
+                                               int64_t ld_out, int64_t r0, int64_t c0) {
   __shared__ bf16_t tile[64][66];
-  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
   const int t = threadIdx.x;
 #pragma unroll
   for (int it = 0; it < 2; ++it) {
@@ -444,6 +467,51 @@ __global__ __launch_bounds__(256) void transpose_kernel(const bf16_t* __restrict
     for (int e = 0; e < 8; ++e) v[e] = tile[rv + e][c];
     *reinterpret_cast<bf16x8*>(out + (c0 + c) * ld_out + r0 + rv) = v;
   }
+}
+
+__global__ __launch_bounds__(256) void transpose_kernel(const bf16_t* __restrict__ in,
+                                                        bf16_t* __restrict__ out, int64_t R,
+                                                        int64_t C, int64_t ld_out) {
+  transpose_tile(in, out, C, ld_out, (int64_t)blockIdx.y * 64, (int64_t)blockIdx.x * 64);
+}
+
+// Several transposes in one launch (the seven weights of a layer: for small layers each launch costs
+// more than its copy).  The argument block is only read with compile-time indices.
+struct TransposeGroup {
+  const bf16_t* in[kMaxTransposeGroup];
+  bf16_t* out[kMaxTransposeGroup];
+  int R[kMaxTransposeGroup], C[kMaxTransposeGroup];
+  int64_t ld_out[kMaxTransposeGroup];
+  int tile_start[kMaxTransposeGroup + 1];
+  int n;
+};
+__global__ __launch_bounds__(256) void transpose_group_kernel(const TransposeGroup g) {
+  const int id = blockIdx.x;
+  const bf16_t* in = g.in[0];
+  bf16_t* out = g.out[0];
+  int C = g.C[0], start = 0;
+  int64_t ld_out = g.ld_out[0];
+#pragma unroll
+  for (int i = 1; i < kMaxTransposeGroup; ++i)
+    if (i < g.n && id >= g.tile_start[i]) { in = g.in[i]; out = g.out[i]; C = g.C[i]; ld_out = g.ld_out[i]; start = g.tile_start[i]; }
+  const int tiles_x = C / 64, tl = id - start;
+  transpose_tile(in, out, C, ld_out, (int64_t)(tl / tiles_x) * 64, (int64_t)(tl % tiles_x) * 64);
+}
+
+int launch_transpose_group(const TransposeJob* jobs, int n, hipStream_t st) {
+  if (n < 1 || n > kMaxTransposeGroup) return fail(-1, "transpose group: 1..%d matrices, got %d", kMaxTransposeGroup, n);
+  TransposeGroup g{};
+  g.n = n;
+  for (int i = 0; i < n; ++i) {
+    g.in[i] = (const bf16_t*)jobs[i].in;
+    g.out[i] = (bf16_t*)jobs[i].out;
+    g.R[i] = (int)jobs[i].R;
+    g.C[i] = (int)jobs[i].C;
+    g.ld_out[i] = jobs[i].ld_out;
+    g.tile_start[i + 1] = g.tile_start[i] + (int)((jobs[i].R / 64) * (jobs[i].C / 64));
+  }
+  hipLaunchKernelGGL(transpose_group_kernel, dim3((unsigned)g.tile_start[n]), dim3(256), 0, st, g);
+  return check_launch("transpose group");
 }
 
 int launch_transpose(const void* in, void* out, int64_t R, int64_t C, int64_t ld_out, hipStream_t st) {

@@ -800,8 +800,10 @@ static int launch_group_cfg(const GemmKArgs* ks, int n, bool ak, bool bk, hipStr
     }                                                                                            \
     hipLaunchKernelGGL(kern, grid, block, lds, st, g);                                           \
   } while (0)
-  // only the layout the weight-gradient products use is instantiated
+  // only the layouts in use are instantiated: the weight-gradient products (both operands mn-major)
+  // and the forward projections (both k-major)
   if (!ak && !bk) GEMM_GROUP_LAUNCH(false, false);
+  else if (ak && bk) GEMM_GROUP_LAUNCH(true, true);
   else return fail(-1, "gemm group: operand layout not built");
 #undef GEMM_GROUP_LAUNCH
   return check_launch("gemm group");

@@ -17,6 +17,9 @@ int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, cons
                        int accumulate, void* workspace, hipStream_t st);
 int launch_rope(void* z, int64_t batch, int64_t seq, int64_t n_heads, int64_t head_dim, float base,
                 int layout, int inverse, hipStream_t st);
+// q and k of a layer in one launch (same positions and angles)
+int launch_rope_pair(void* q, void* k, int64_t batch, int64_t seq, int64_t n_q_heads, int64_t n_kv_heads,
+                     int64_t head_dim, float base, int layout, int inverse, hipStream_t st);
 int launch_swiglu_fwd(const void* g, const void* u, int64_t n, void* a, hipStream_t st);
 int launch_swiglu_bwd(const void* g, const void* u, const void* da, int64_t n, void* dg, void* du,
                       hipStream_t st);
@@ -27,6 +30,10 @@ int launch_swiglu_bwd_rows(const void* g, const void* u, const void* da, int64_t
                            int64_t ld_p, void* dg, void* du, hipStream_t st);
 // out[c][r] = in[r][c]; out has leading dimension ld_out >= R
 int launch_transpose(const void* in, void* out, int64_t R, int64_t C, int64_t ld_out, hipStream_t st);
+// up to 8 transposes (each R, C multiples of 64) in one launch
+constexpr int kMaxTransposeGroup = 8;
+struct TransposeJob { const void* in; void* out; int64_t R, C, ld_out; };
+int launch_transpose_group(const TransposeJob* jobs, int n, hipStream_t st);
 int launch_embed_fwd(const void* table, const int64_t* ids, int64_t T, int64_t V, int64_t D,
                      void* x0, hipStream_t st);
 int launch_embed_bwd(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D,
@@ -54,8 +61,8 @@ struct GemmArgs {
   bool a_kmajor, b_kmajor;
 };
 int launch_gemm(const GemmArgs& g, hipStream_t st);
-// Up to 8 independent problems with the same a_kmajor/b_kmajor in one launch (only the layout of
-// the weight-gradient product, both operands mn-major, is built).
+// Up to 8 independent problems with the same a_kmajor/b_kmajor in one launch (built for both operands
+// mn-major, the weight-gradient products, and both k-major, the forward projections).
 int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st);
 // g = x Wg^T, u = x Wu^T and a = silu(g) * u (from the rounded g, u) in one launch.  x [T, K] with
 // leading dimension ldx, wg and wu [F, K] with ldw, g and u with ldgu, a with lda.  Only shapes
