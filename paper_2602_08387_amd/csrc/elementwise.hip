@@ -549,14 +549,18 @@ __global__ __launch_bounds__(256) void zero_kernel(u32x4* p, int64_t nvec) {
     p[i] = z;
 }
 
-// One block per token t.  The block scans all ids; it owns row ids[t] iff no earlier token has
-// the same id, and then sums (fp32, token order) the gradient rows of every token with that id.
+// One block per token t.  The block owns row ids[t] iff no earlier token has the same id; it then
+// sums (fp32, ascending token order: the result does not depend on scheduling) the gradient rows of
+// every token with that id.  The tokens are scanned in segments of kEmbSeg: all threads mark the
+// matches of a segment in an LDS bitmap (atomic OR, so the bitmap is the same however the threads are
+// scheduled), then every thread walks the set bits in order for its columns.
+constexpr int kEmbSeg = 8192;
 __global__ __launch_bounds__(256) void embed_bwd_kernel(const bf16_t* __restrict__ dx0,
                                                         const int64_t* __restrict__ ids,
                                                         bf16_t* __restrict__ dtable, int64_t T,
                                                         int64_t V, int D) {
   __shared__ int earlier;
-  __shared__ int match[1024];
+  __shared__ unsigned bits[kEmbSeg / 32];
   const int64_t t = blockIdx.x;
   const int64_t id = ids[t];
   if (id < 0 || id >= V) return;  // uniform over the block
@@ -567,32 +571,65 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(const bf16_t* __restrict
   __syncthreads();
   if (earlier) return;            // uniform over the block
   const int nv = D >> 3;
+  constexpr int NC = 2;           // column vectors per thread and pass: D up to 4096 in one pass
   bf16x8* out = reinterpret_cast<bf16x8*>(dtable + id * D);
-  for (int c0 = 0; c0 < nv; c0 += blockDim.x) {
-    const int c = c0 + threadIdx.x;
-    float a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int64_t base = t; base < T; base += 1024) {
+  for (int c0 = 0; c0 < nv; c0 += NC * 256) {
+    float a[NC][8];
+#pragma unroll
+    for (int q = 0; q < NC; ++q)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[q][e] = 0.f;
+    for (int64_t base = t - t % kEmbSeg; base < T; base += kEmbSeg) {
       __syncthreads();
-      for (int k = threadIdx.x; k < 1024; k += blockDim.x) {
+      for (int w = threadIdx.x; w < kEmbSeg / 32; w += 256) bits[w] = 0u;
+      __syncthreads();
+      for (int k = threadIdx.x; k < kEmbSeg; k += 256) {
         const int64_t s = base + k;
-        match[k] = (s < T && ids[s] == id) ? 1 : 0;
+        if (s >= t && s < T && ids[s] == id) atomicOr(&bits[k >> 5], 1u << (k & 31));
       }
       __syncthreads();
-      if (c < nv) {
-        for (int k = 0; k < 1024; ++k) {
-          if (match[k]) {
-            bf16x8 v = reinterpret_cast<const bf16x8*>(dx0 + (base + k) * D)[c];
+      // one row ahead: the loads of the next matching row go out before the current one is summed
+      // (a frequent token has thousands of rows, all summed by this one workgroup)
+      bf16x8 cur[NC], nxt[NC];
+      bool have = false;
+      auto add_cur = [&]() {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) a[e] += (float)v[e];
+        for (int q = 0; q < NC; ++q) {
+          const int c = c0 + q * 256 + threadIdx.x;
+          if (c < nv) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a[q][e] += (float)cur[q][e];
           }
         }
-      }
-    }
-    if (c < nv) {
-      bf16x8 o;
+      };
+      for (int w = 0; w < kEmbSeg / 32; ++w) {
+        unsigned m = bits[w];
+        while (m) {
+          const int k = w * 32 + __builtin_ctz(m);
+          m &= m - 1;
+          const bf16x8* row = reinterpret_cast<const bf16x8*>(dx0 + (base + k) * D);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)a[e];
-      out[c] = o;
+          for (int q = 0; q < NC; ++q) {
+            const int c = c0 + q * 256 + threadIdx.x;
+            if (c < nv) nxt[q] = row[c];
+          }
+          if (have) add_cur();
+#pragma unroll
+          for (int q = 0; q < NC; ++q) cur[q] = nxt[q];
+          have = true;
+        }
+      }
+      if (have) add_cur();
+    }
+#pragma unroll
+    for (int q = 0; q < NC; ++q) {
+      const int c = c0 + q * 256 + threadIdx.x;
+      if (c < nv) {
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)a[q][e];
+        out[c] = o;
+      }
     }
   }
 }

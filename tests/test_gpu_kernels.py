@@ -376,23 +376,32 @@ def test_ce_zero_logits_gives_log_vocab(K):
 
 
 # ------------------------------------------------------------------ embedding
-def test_embedding_forward_backward(K):
+@pytest.mark.parametrize("V,D,T", [
+    (1000, 256, 700),
+    (50, 64, 20000),        # every row summed over ~400 tokens spread over three scan segments of 8192
+    (3000, 4096, 1024),     # the widest row: two column vectors per thread
+    (128256, 512, 8192),    # vocabulary and token count of the stack workload, uniform ids
+])
+def test_embedding_forward_backward(K, V, D, T):
     rng = np.random.default_rng(9)
-    V, D, T = 1000, 256, 700
     ids = rng.integers(0, V, T)
     ids[:50] = 7          # heavy duplicate
-    ids[600:] = ids[100:200]
+    ids[T - 100:] = ids[100:200]
     Eb, db = _rand_bits(rng, (V, D), 0.02), _rand_bits(rng, (T, D))
     Ed, dd, idd = dev_bf16(Eb), dev_bf16(db), torch.from_numpy(ids).cuda()
     x0 = torch.empty(T, D, dtype=torch.bfloat16, device="cuda")
     K.embed_forward(Ed, idd, T, V, D, x0)
     assert torch.equal(x0.view(torch.int16), Ed[idd].view(torch.int16))
+    del Ed, x0
     dE = torch.full((V, D), float("nan"), dtype=torch.bfloat16, device="cuda")
     K.embed_backward(dd, idd, T, V, D, dE)
     ref = olm.embed_bwd(si.bf16_bits_to_f64(db), ids, V)
     assert_close(dE, ref, "dE", rel_tol=6e-3)
     absent = np.setdiff1d(np.arange(V), ids)
     assert np.all(host_f64(dE)[absent] == 0)
+    dE2 = torch.full((V, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    K.embed_backward(dd, idd, T, V, D, dE2)
+    assert torch.equal(dE.view(torch.int16), dE2.view(torch.int16)), "scatter-add is not run-to-run bitwise stable"
 
 
 # ------------------------------------------------------------------ argument checking (host side only)
