@@ -85,7 +85,7 @@ def main():
                          "counters of a profiler run are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures the single-GPU decoder-layer step; this build has no multi-GPU path "
+        print("bench.py measures the single-GPU decoder-layer step; this library has no multi-GPU path "
               "(no collectives, no sharding): run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
