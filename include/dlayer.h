@@ -112,6 +112,24 @@ size_t ce_loss_workspace_bytes(int64_t T, int64_t V);
 int ce_loss_fwd_bwd(const void* logits, const int64_t* targets, int64_t T, int64_t V,
                     float grad_scale, float* loss, void* dlogits, void* workspace, void* stream);
 
+/*
+ * The LM head and its loss in one call, without ever holding all T x V logits (same training loss):
+ *   logits = h w_lm^T;  loss, dlogits as in ce_loss_fwd_bwd;  dh = dlogits w_lm;  dw_lm (+)= dlogits^T h
+ * The rows are walked in chunks of chunk_rows (0 = chosen by the library: about 1 GiB of logits):
+ * each chunk's logits are formed, turned into their gradient in place and consumed by the two
+ * gradient products before the next chunk overwrites them.  dw_lm is accumulated in bf16 from chunk
+ * to chunk (fp32 within a chunk), so it is rounded once per chunk instead of once.
+ * h, dh [T, D], w_lm, dw_lm [V, D] bf16, targets [T] int64, *loss device f32.  T, D, V multiples of
+ * 64; chunk_rows 0 or a multiple of 64; one chunk of logits and every operand below 4 GiB (T * V
+ * itself may exceed it).  accumulate_dw as in dlayer_backward.
+ * workspace: lm_head_ce_workspace_bytes(T, D, V, chunk_rows) - one chunk of logits, a transposed
+ * copy of w_lm and T floats.
+ */
+size_t lm_head_ce_workspace_bytes(int64_t T, int64_t D, int64_t V, int64_t chunk_rows);
+int lm_head_ce_fwd_bwd(const void* h, const void* w_lm, const int64_t* targets, int64_t T, int64_t D,
+                       int64_t V, float grad_scale, int64_t chunk_rows, float* loss, void* dh,
+                       void* dw_lm, int accumulate_dw, void* workspace, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Building blocks (the steps of the layer, exposed for the model stack around it: embedding,
  * final norm, LM head - and for step-by-step verification).

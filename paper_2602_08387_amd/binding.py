@@ -12,6 +12,7 @@ WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w
 EXPORTED_SYMBOLS = (
     "dlayer_version", "dlayer_last_error", "dlayer_saved_bytes", "dlayer_workspace_bytes",
     "dlayer_forward", "dlayer_backward", "ce_loss_workspace_bytes", "ce_loss_fwd_bwd",
+    "lm_head_ce_workspace_bytes", "lm_head_ce_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward_workspace_bytes", "rmsnorm_backward",
     "linear_forward", "linear_swiglu_forward", "linear_swiglu_backward_workspace_bytes",
     "linear_swiglu_backward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
@@ -60,6 +61,8 @@ def _load():
         "dlayer_forward": (C.c_int, [cfgp, vp, ptrs, vp, vp, vp, vp]),
         "dlayer_backward": (C.c_int, [cfgp, vp, ptrs, vp, vp, vp, ptrs, C.c_int, vp, vp]),
         "ce_loss_workspace_bytes": (sz, [i64, i64]),
+        "lm_head_ce_workspace_bytes": (sz, [i64, i64, i64, i64]),
+        "lm_head_ce_fwd_bwd": (C.c_int, [vp, vp, vp, i64, i64, i64, C.c_float, i64, vp, vp, vp, C.c_int, vp, vp]),
         "ce_loss_fwd_bwd": (C.c_int, [vp, vp, i64, i64, f32, vp, vp, vp, vp]),
         "rmsnorm_forward": (C.c_int, [vp, vp, i64, i64, f32, vp, vp, vp]),
         "rmsnorm_backward_workspace_bytes": (sz, [i64, i64]),
@@ -142,6 +145,16 @@ def dlayer_backward(cfg, x, weights, dy, saved, dx, wgrads, accumulate_wgrads, w
 
 def ce_loss_workspace_bytes(T, V) -> int:
     return lib.ce_loss_workspace_bytes(T, V)
+
+
+def lm_head_ce_workspace_bytes(T, D, V, chunk_rows=0) -> int:
+    return lib.lm_head_ce_workspace_bytes(T, D, V, chunk_rows)
+
+
+def lm_head_ce_fwd_bwd(h, w_lm, targets, T, D, V, grad_scale, chunk_rows, loss, dh, dw_lm, accumulate_dw, workspace,
+                       stream=None):
+    _check(lib.lm_head_ce_fwd_bwd(_p(h), _p(w_lm), _p(targets), T, D, V, grad_scale, chunk_rows, _p(loss), _p(dh),
+                                  _p(dw_lm), int(accumulate_dw), _p(workspace), _stream(stream)), "lm_head_ce_fwd_bwd")
 
 
 def ce_loss_fwd_bwd(logits, targets, T, V, grad_scale, loss, dlogits, workspace, stream=None):

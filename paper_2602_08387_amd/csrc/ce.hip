@@ -126,20 +126,29 @@ __global__ __launch_bounds__(1024) void mean_kernel(const float* __restrict__ v,
 
 size_t ce_workspace(int64_t T, int64_t) { return (size_t)T * sizeof(float); }
 
-int launch_ce(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
-              float* loss, void* dlogits, void* workspace, hipStream_t st) {
-  const float scale = grad_scale / (float)T;
-  float* row_loss = (float*)workspace;
+// rows [0, rows) of a larger problem: per-row losses into row_loss, gradient scaled by `scale`
+int launch_ce_rows(const void* logits, const int64_t* targets, int64_t rows, int64_t V, float scale, float* row_loss,
+                   void* dlogits, hipStream_t st) {
   if (V <= (int64_t)kCeThreads * 8 * 16)
-    hipLaunchKernelGGL(ce_kernel<true>, dim3((unsigned)T), dim3(kCeThreads), 0, st,
+    hipLaunchKernelGGL(ce_kernel<true>, dim3((unsigned)rows), dim3(kCeThreads), 0, st,
                        (const bf16_t*)logits, targets, V, scale, row_loss, (bf16_t*)dlogits);
   else
-    hipLaunchKernelGGL(ce_kernel<false>, dim3((unsigned)T), dim3(kCeThreads), 0, st,
+    hipLaunchKernelGGL(ce_kernel<false>, dim3((unsigned)rows), dim3(kCeThreads), 0, st,
                        (const bf16_t*)logits, targets, V, scale, row_loss, (bf16_t*)dlogits);
-  int rc = check_launch("ce_loss_fwd_bwd");
-  if (rc) return rc;
-  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, st, (const float*)row_loss, T, loss);
+  return check_launch("ce_loss_fwd_bwd");
+}
+
+int launch_ce_mean(const float* row_loss, int64_t T, float* loss, hipStream_t st) {
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, st, row_loss, T, loss);
   return check_launch("ce_loss_fwd_bwd(mean)");
+}
+
+int launch_ce(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
+              float* loss, void* dlogits, void* workspace, hipStream_t st) {
+  float* row_loss = (float*)workspace;
+  int rc = launch_ce_rows(logits, targets, T, V, grad_scale / (float)T, row_loss, dlogits, st);
+  if (rc) return rc;
+  return launch_ce_mean(row_loss, T, loss, st);
 }
 
 }  // namespace dl

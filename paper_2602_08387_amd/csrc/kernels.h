@@ -89,5 +89,9 @@ int launch_attention_bwd(const void* q, const void* k, const void* v, const void
 size_t ce_workspace(int64_t T, int64_t V);
 int launch_ce(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
               float* loss, void* dlogits, void* workspace, hipStream_t st);
+// the two halves of launch_ce, for callers that walk the rows in chunks
+int launch_ce_rows(const void* logits, const int64_t* targets, int64_t rows, int64_t V, float scale, float* row_loss,
+                   void* dlogits, hipStream_t st);
+int launch_ce_mean(const float* row_loss, int64_t T, float* loss, hipStream_t st);
 
 }  // namespace dl

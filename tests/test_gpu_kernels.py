@@ -366,6 +366,48 @@ def test_ce_loss(K, T, V, alias):
     assert np.all(np.abs(got[idx, tg] - dlg_ref[idx, tg]) <= 1e-2 * np.abs(dlg_ref[idx, tg]))
 
 
+@pytest.mark.parametrize("T,D,V,chunk", [
+    (512, 128, 1024, 0),        # one chunk
+    (832, 192, 4160, 256),      # three full chunks and a ragged one of 64 rows
+    (1024, 256, 8000, 384),     # chunk size that is not a multiple of the 256-row tile
+])
+def test_lm_head_ce_chunked(K, T, D, V, chunk):
+    """LM head + mean cross-entropy without the full logits: against the oracle, and against the
+    unfused route (linear_forward, ce_loss_fwd_bwd, linear_backward) on the same device data."""
+    rng = np.random.default_rng(T + V)
+    hb, wb = _rand_bits(rng, (T, D)), _rand_bits(rng, (V, D), 0.05)
+    tg = rng.integers(0, V, T)
+    h, w = si.bf16_bits_to_f64(hb), si.bf16_bits_to_f64(wb)
+    gs = 3.0
+    loss_ref, dlog_ref, _ = olm.ce_loss_fwd_bwd(h @ w.T, tg, grad_scale=gs)
+    hd, wd, tgd = dev_bf16(hb), dev_bf16(wb), torch.from_numpy(tg).cuda()
+    loss = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    dh = torch.full((T, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dw = torch.full((V, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = _ws(K.lm_head_ce_workspace_bytes(T, D, V, chunk))
+    K.lm_head_ce_fwd_bwd(hd, wd, tgd, T, D, V, gs, chunk, loss, dh, dw, 0, ws)
+    assert abs(float(loss) - loss_ref) <= 2e-3 * abs(loss_ref)
+    dh_ref, dw_ref = dlog_ref @ w, dlog_ref.T @ h
+    # gradients: the cosine is the bar; the element-wise bound is loose because the operand dlogits is
+    # itself rounded to bf16 and dw_lm is rounded once per chunk
+    assert_close(dh, dh_ref, "dh", rel_tol=5e-2)
+    assert_close(dw, dw_ref, "dw_lm", rel_tol=5e-2)
+    assert cosine(host_f64(dh), dh_ref) > 0.9999 and cosine(host_f64(dw), dw_ref) > 0.9999
+    # unfused route: same kernels on the whole T x V logits
+    logits = torch.empty(T, V, dtype=torch.bfloat16, device="cuda")
+    K.linear_forward(hd, wd, None, T, D, V, logits)
+    loss2 = torch.zeros(1, dtype=torch.float32, device="cuda")
+    K.ce_loss_fwd_bwd(logits, tgd, T, V, gs, loss2, logits, _ws(K.ce_loss_workspace_bytes(T, V)))
+    dh2, dw2 = torch.empty_like(dh), torch.empty_like(dw)
+    K.linear_backward(hd, wd, logits, T, D, V, dh2, dw2, 0, _ws(K.linear_backward_workspace_bytes(T, D, V)))
+    assert abs(float(loss) - float(loss2)) <= 1e-6 * abs(float(loss2)) + 1e-7
+    assert torch.equal(dh.view(torch.int16), dh2.view(torch.int16)), "dh: chunked and whole-matrix routes differ"
+    assert_close(dw, host_f64(dw2), "dw_lm vs unfused", rel_tol=5e-2)   # dw is rounded once per chunk, as with accumulate_dw
+    # accumulate_dw adds to what is there
+    K.lm_head_ce_fwd_bwd(hd, wd, tgd, T, D, V, gs, chunk, loss, dh, dw, 1, ws)
+    assert_close(dw, 2 * dw_ref, "dw_lm accumulated", rel_tol=5e-2)
+
+
 def test_ce_zero_logits_gives_log_vocab(K):
     T, V = 16, si.VOCAB_8B
     ld = torch.zeros(T, V, dtype=torch.bfloat16, device="cuda")

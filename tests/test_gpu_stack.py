@@ -22,9 +22,12 @@ def _buf(n):
     return torch.full((max(int(n), 256),), 0xFF, dtype=torch.uint8, device="cuda")
 
 
-def run_stack(K, cfg, raw, V, grad_scale=1.0, keep_rows=None):
+def run_stack(K, cfg, raw, V, grad_scale=1.0, keep_rows=None, head_chunk_rows=None):
     """Pointer plumbing only: every arithmetic step is a library call.  keep_rows: zero the upstream
-    gradient (dlogits) of all token rows from that index on before the backward pass."""
+    gradient (dlogits) of all token rows from that index on before the backward pass.
+    head_chunk_rows: run the LM head and its loss through lm_head_ce_fwd_bwd with that chunk size
+    (the logits are then never held whole) instead of linear_forward / ce_loss_fwd_bwd /
+    linear_backward."""
     B, S, D = cfg.batch, cfg.seq, cfg.d_model
     T, L = B * S, len(raw["layers"])
     ids = torch.from_numpy(raw["ids"].reshape(-1)).cuda()
@@ -40,15 +43,21 @@ def run_stack(K, cfg, raw, V, grad_scale=1.0, keep_rows=None):
         K.dlayer_forward(cfg, xs[l], W[l], xs[l + 1], saved[l], ws)
     h_f, rstd_f = bf(T, D), torch.empty(T, dtype=torch.float32, device="cuda")
     K.rmsnorm_forward(xs[L], g_f, T, D, cfg.rms_eps, h_f, rstd_f)
-    logits = bf(T, V)
-    K.linear_forward(h_f, w_lm, None, T, D, V, logits)
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
-    logits_prefix = logits[:keep_rows].clone() if keep_rows else None
-    K.ce_loss_fwd_bwd(logits, tgt, T, V, grad_scale, loss, logits, _buf(K.ce_loss_workspace_bytes(T, V)))  # in place
-    if keep_rows:
-        logits[keep_rows:].zero_()
     dh_f, dw_lm = bf(T, D), bf(V, D)
-    K.linear_backward(h_f, w_lm, logits, T, D, V, dh_f, dw_lm, 0, _buf(K.linear_backward_workspace_bytes(T, D, V)))
+    logits_prefix = None
+    if head_chunk_rows is not None:
+        assert keep_rows is None
+        K.lm_head_ce_fwd_bwd(h_f, w_lm, tgt, T, D, V, grad_scale, head_chunk_rows, loss, dh_f, dw_lm, 0,
+                             _buf(K.lm_head_ce_workspace_bytes(T, D, V, head_chunk_rows)))
+    else:
+        logits = bf(T, V)
+        K.linear_forward(h_f, w_lm, None, T, D, V, logits)
+        logits_prefix = logits[:keep_rows].clone() if keep_rows else None
+        K.ce_loss_fwd_bwd(logits, tgt, T, V, grad_scale, loss, logits, _buf(K.ce_loss_workspace_bytes(T, V)))  # in place
+        if keep_rows:
+            logits[keep_rows:].zero_()
+        K.linear_backward(h_f, w_lm, logits, T, D, V, dh_f, dw_lm, 0, _buf(K.linear_backward_workspace_bytes(T, D, V)))
     dx, dg_f = bf(T, D), bf(D)
     K.rmsnorm_backward(xs[L], g_f, rstd_f, dh_f, None, T, D, dx, dg_f, 0, _buf(K.rmsnorm_backward_workspace_bytes(T, D)))
     dW = [{n: torch.full_like(t, float("nan")) for n, t in W[l].items()} for l in range(L)]
@@ -63,7 +72,8 @@ def run_stack(K, cfg, raw, V, grad_scale=1.0, keep_rows=None):
             "logits_prefix": logits_prefix}
 
 
-def test_stack_matches_oracle(K):
+@pytest.mark.parametrize("head_chunk_rows", [None, 192])
+def test_stack_matches_oracle(K, head_chunk_rows):
     cfg = si.LayerConfig(2, 256, 256, 4, 2, 64, 512, 1e-5, 500000.0, 0)
     V, L = 4096, 3
     raw = si.make_stack_inputs(cfg, L, V, seed=0)
@@ -72,7 +82,7 @@ def test_stack_matches_oracle(K):
     args = (cfg, s["ids"], s["targets"], s["embed"], s["layers"], s["g_final"], s["w_lm"])
     st = olm.stack_forward(*args)
     ref = olm.stack_backward(*args, st)
-    got = run_stack(K, cfg, raw, V)
+    got = run_stack(K, cfg, raw, V, head_chunk_rows=head_chunk_rows)
     assert abs(got["loss"] - st["loss"]) <= 2e-2 * abs(st["loss"]), (got["loss"], st["loss"])
     assert abs(got["loss"] - st["loss"]) <= 2e-3 * abs(st["loss"])   # what the arithmetic actually gives
     # the stack's bar is on the scalar loss; the hidden state after three layers carries three layers
