@@ -406,9 +406,13 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
   }
   if (tl.total >= 2) wait_vmcnt<LPW>(); else wait_vmcnt<0>();
 
+  // K-step s of a tile lives in ring stage (s + par) & 1: the K-steps of successive tiles form one
+  // stream through the ring, so `par` moves on by the tile's number of K-steps.
+  int par = 0;
   while (true) {
-    const Tile p = tl;   // this tile; `tl` moves on to the next one before the epilogue
+    const Tile p = tl;   // this tile; `tl` moves on to the next one during its last K-steps
     const int m0 = tl.m0, n0 = tl.n0, total = tl.total;
+    bool early = false;
     acc_t acc[FN][FM];
 #pragma unroll
     for (int i = 0; i < FN; ++i)
@@ -428,7 +432,7 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
     constexpr int KK = BK / KSTEP;
     bf16x8 fa[2][FM], fb[2][FN];
     {
-      const char* ta = smem;
+      const char* ta = smem + par * STAGE;
       const char* tb = ta + A_BYTES;
 #pragma unroll
       for (int j = 0; j < FM; ++j) fa[0][j] = read_frag<BM, AK>(ta, wave_m * TM + j * MI, 0, lane);
@@ -437,7 +441,14 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
     }
     if constexpr (!(AK && BKM)) wait_frags<FM, FN>(fa[0], fb[0]);
     for (int t = 0; t < total; ++t) {
-      char* st_cur = smem + (t & 1) * STAGE;
+      // Every load of this tile is out once its last but one K-step begins.  The cursor moves on to the
+      // workgroup's next tile there, and that tile's first two K-steps go out at this tile's last two
+      // hand-overs like any other refill: by the time the epilogue runs they have had a K-step to land.
+      if (t == total - 2 && id + (int)gridDim.x < ntiles) {
+        tl = locate(id + gridDim.x);
+        early = true;
+      }
+      char* st_cur = smem + ((t + par) & 1) * STAGE;
       const char* ta = st_cur;
       const char* tb = ta + A_BYTES;
       static_for<0, KK>([&](auto kk_c) {
@@ -458,11 +469,11 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
             // every wave now holds its last fragments of stage t in registers: refill that stage with
             // step t+2 right away, so the loads get a whole K-step to land (measured global -> LDS
             // latency under load: about 1800 cycles against a K-step of about 3000)
-            if (loader) cur.issue_next(one, st_cur, wave, m0, n0, lane);
+            if (loader) cur.issue_next(one, st_cur, wave, tl.m0, tl.n0, lane);
             // the reads go out unconditionally (after the last K-step they fetch stale bytes nobody
             // uses), which keeps them in one block with this group's MFMAs so that the scheduler
             // interleaves them (+2 %)
-            const char* na = smem + ((t + 1) & 1) * STAGE;
+            const char* na = smem + ((t + 1 + par) & 1) * STAGE;
             const char* nbp = na + A_BYTES;
 #pragma unroll
             for (int j = 0; j < FM; ++j) fa[nb][j] = read_frag<BM, AK>(na, wave_m * TM + j * MI, 0, lane);
@@ -491,7 +502,7 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
           constexpr bool GEMM_SPREAD_LOADS = true;
           constexpr int NF = FM + FN;                       // fragments to fetch: A 0..FM-1, then B
           constexpr int NCH = last ? FN - 1 : FN;           // chunks they are spread over
-          const char* ra_ = last ? smem + ((t + 1) & 1) * STAGE : ta;
+          const char* ra_ = last ? smem + ((t + 1 + par) & 1) * STAGE : ta;
           const char* rb_ = ra_ + A_BYTES;
           const bool do_reads = !last || t + 1 < total;
           static_for<0, FN>([&](auto i_c) {
@@ -501,10 +512,10 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
               asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
               __builtin_amdgcn_s_barrier();
               asm volatile("" ::: "memory");
-              if (!GEMM_SPREAD_LOADS && loader) cur.issue_next(one, st_cur, wave, m0, n0, lane);   // step t+2 into the drained stage
+              if (!GEMM_SPREAD_LOADS && loader) cur.issue_next(one, st_cur, wave, tl.m0, tl.n0, lane);   // step t+2 into the drained stage
             }
             if constexpr (GEMM_SPREAD_LOADS && last && i >= 1) {
-              if (loader) cur.template issue_piece<i - 1, FN - 1>(one, st_cur, wave, m0, n0, lane);
+              if (loader) cur.template issue_piece<i - 1, FN - 1>(one, st_cur, wave, tl.m0, tl.n0, lane);
             }
               const int ch = last ? i - 1 : i;
             if (ch >= 0 && do_reads) {
@@ -524,18 +535,17 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
         }
       });
     }
-    // (the hand-over of the last K-step waited for every load and passed a barrier after every wave's
-    // last LDS read: the whole ring is free here)
-
-    // Next tile: open its cursor and send its first two K-steps into the ring before the epilogue
-    // starts.
+    // Next tile.  Normally its cursor was opened and its first two K-steps sent during the last two
+    // K-steps above; a tile of a single K-step sends them here (the last hand-over waited for every
+    // load and passed a barrier after every wave's last LDS read: the whole ring is free).
     id += gridDim.x;
     const bool more = id < ntiles;
-    if (more) {
+    par = (par + total) & 1;
+    if (more && !early) {
       tl = locate(id);
       if (loader) {
-        cur.issue_next(one, smem, wave, tl.m0, tl.n0, lane);
-        cur.issue_next(one, smem + STAGE, wave, tl.m0, tl.n0, lane);
+        cur.issue_next(one, smem + par * STAGE, wave, tl.m0, tl.n0, lane);
+        cur.issue_next(one, smem + (par ^ 1) * STAGE, wave, tl.m0, tl.n0, lane);
       }
     }
 
