@@ -8,6 +8,13 @@
 namespace dl {
 
 constexpr int kCeThreads = 1024;
+constexpr float kCeLog2e = 1.4426950408889634f;
+// exp(x - m) as one FMA and one v_exp_f32: 2^(x * log2(e) - m * log2(e)); results below 2^-126 flush to
+// zero, which is what a softmax weight that small should be anyway.  The kernel is bound by its vector
+// arithmetic (two exponentials and three conversions per logit), so instructions per element count.
+__device__ __forceinline__ float exp_shifted(float x, float m_log2e) {
+  return __builtin_amdgcn_exp2f(__builtin_fmaf(x, kCeLog2e, -m_log2e));
+}
 
 __device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -58,6 +65,7 @@ __global__ __launch_bounds__(kCeThreads) void ce_kernel(const bf16_t* logits,
     }
   }
   mx = block_reduce(mx, true, red);
+  const float mx2 = mx * kCeLog2e;
   float sum = 0.f;
   if constexpr (CACHED) {
 #pragma unroll
@@ -65,45 +73,46 @@ __global__ __launch_bounds__(kCeThreads) void ce_kernel(const bf16_t* logits,
       const int c = i * kCeThreads + threadIdx.x;
       if (c < nvec) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sum += __expf((float)v[i][e] - mx);
+        for (int e = 0; e < 8; ++e) sum += exp_shifted((float)v[i][e], mx2);
       }
     }
   } else {
     for (int c = threadIdx.x; c < nvec; c += kCeThreads) {
       bf16x8 t = in[c];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sum += __expf((float)t[e] - mx);
+      for (int e = 0; e < 8; ++e) sum += exp_shifted((float)t[e], mx2);
     }
   }
   sum = block_reduce(sum, false, red);  // its barriers also order every read before any write
   const float lse = mx + __logf(sum);
   if (threadIdx.x == 0) row_loss[row] = tgt_ok ? lse - picked_s : lse;
   const int tc = tgt_ok ? (int)(tgt >> 3) : -1, te = (int)(tgt & 7);
+  const float lse2 = lse * kCeLog2e;
+  // gradient of one 8-vector, without the -1 of the target: the thread that owns the target's vector
+  // stores that one element again after its vector (same thread, same address: in order), from the
+  // logit saved at the start - a store under a rarely taken branch instead of a select per element
+  auto grad_vec = [&](const bf16x8& x) {
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (bf16_t)(exp_shifted((float)x[e], lse2) * scale);
+    return o;
+  };
+  auto fix_target = [&](int c) {
+    if (c == tc) dlogits[row * V + tgt] = (bf16_t)((exp_shifted(picked_s, lse2) - 1.0f) * scale);
+  };
   if constexpr (CACHED) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = i * kCeThreads + threadIdx.x;
       if (c < nvec) {
-        bf16x8 o;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          float pr = __expf((float)v[i][e] - lse);
-          if (c == tc && e == te) pr -= 1.0f;
-          o[e] = (bf16_t)(pr * scale);
-        }
-        out[c] = o;
+        out[c] = grad_vec(v[i]);
+        fix_target(c);
       }
     }
   } else {
     for (int c = threadIdx.x; c < nvec; c += kCeThreads) {
-      bf16x8 t = in[c], o;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float pr = __expf((float)t[e] - lse);
-        if (c == tc && e == te) pr -= 1.0f;
-        o[e] = (bf16_t)(pr * scale);
-      }
-      out[c] = o;
+      out[c] = grad_vec(in[c]);
+      fix_target(c);
     }
   }
 }
