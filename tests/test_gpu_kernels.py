@@ -102,7 +102,11 @@ def test_swiglu(K):
     (2048, 4096, 4096, False), (4096, 1024, 5632, True),
     # more 256x256 tiles than CUs with ragged last tile rows and columns: every persistent workgroup
     # walks several tiles, some of them partly outside the matrix
-    (5000, 512, 5064, True), (4100, 256, 4360, False)])
+    (5000, 512, 5064, True), (4100, 256, 4360, False),
+    # several tiles per workgroup with an odd number of K-steps (3, 1, 5): the ring stage a tile starts
+    # in alternates from tile to tile; with one K-step the next tile's loads go out after the loop,
+    # with two they go out during the very first K-step.  The last one runs on the 128 x 128 tiles.
+    (8192, 192, 4096, False), (8192, 64, 4096, True), (8192, 128, 4200, False), (2048, 320, 5000, True)])
 def test_linear_forward(K, T, Kd, N, res):
     rng = np.random.default_rng(T + N)
     xb, wb, rb = _rand_bits(rng, (T, Kd)), _rand_bits(rng, (N, Kd), 0.05), _rand_bits(rng, (T, N))
