@@ -141,6 +141,17 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
     n_sub = max(3, args.steps // 2)
+    # per-step spread (informational): one event pair per step
+    evs = []
+    for _ in range(max(5, args.steps)):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        step()
+        b.record()
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in evs)
+    step_median_ms, step_min_ms = per_step[len(per_step) // 2], per_step[0]
     fwd_ms = timed(lambda: K.dlayer_forward(cfg, x, w, y, saved, ws), n_sub)
     bwd_ms = timed(lambda: K.dlayer_backward(cfg, x, w, dy, saved, dx, dw, 0, ws), n_sub)
 
@@ -185,6 +196,7 @@ def main():
                    "flops_per_step": flops},
         "tokens_per_s": cfg.tokens / (ms * 1e-3), "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "peak_tflops": PEAK_BF16_TFLOPS, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "ms_per_step_median": step_median_ms, "ms_per_step_min": step_min_ms,
         "paper_throughput": "not reported in the paper's text (Fig. 2b is an image; 8B Llama-3, Leonardo)",
         "roofline": roofline,
     }
