@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b"])
+    ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b", "70b_width"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=4096)
     ap.add_argument("--copy-probe", action="store_true",

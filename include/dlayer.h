@@ -31,7 +31,7 @@
  *   - Shape granularity: head_dim in {32, 64, 128}; n_q_heads % n_kv_heads == 0; seq a
  *     multiple of 128; every contraction (inner) dimension a multiple of 64 (for a layer:
  *     d_model, d_ff, n_q_heads*head_dim, n_kv_heads*head_dim and batch*seq) and every output
- *     feature dimension a multiple of 8; d_model <= 4096; feature counts of the element-wise
+ *     feature dimension a multiple of 8; d_model <= 16384; feature counts of the element-wise
  *     kernels a multiple of 8; every tensor smaller than 4 GiB.
  */
 #ifndef DLAYER_H

@@ -72,7 +72,7 @@ static const char* cfg_problem(const dlayer_cfg* c) {
   if (c->d_model % 64 || c->d_ff % 64) return "d_model and d_ff must be multiples of 64";
   if ((c->n_q_heads * c->head_dim) % 64 || (c->n_kv_heads * c->head_dim) % 64)
     return "n_q_heads*head_dim and n_kv_heads*head_dim must be multiples of 64";
-  if (c->d_model > 4096) return "d_model above 4096 is not supported";
+  if (c->d_model > 16384) return "d_model above 16384 is not supported";
   if (c->rope_layout != 0 && c->rope_layout != 1) return "rope_layout must be 0 or 1";
   if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return "rms_eps must be >= 0 and rope_base > 0";
   const int64_t T = (int64_t)c->batch * c->seq;
@@ -383,7 +383,7 @@ size_t rmsnorm_backward_workspace_bytes(int64_t T, int64_t D) { return T > 0 && 
 int rmsnorm_backward(const void* x, const void* gamma, const float* rstd, const void* dh, const void* dres,
                      int64_t T, int64_t D, void* dx, void* dgamma, int accumulate_dgamma, void* workspace,
                      void* stream) {
-  REQUIRE(T > 0 && D > 0 && D % 8 == 0 && D <= 4096, "rmsnorm_backward: need T > 0, D %% 8 == 0, D <= 4096");
+  REQUIRE(T > 0 && D > 0 && D % 8 == 0 && D <= 16384, "rmsnorm_backward: need T > 0, D %% 8 == 0, D <= 16384");
   REQUIRE_PTR(x); REQUIRE_PTR(gamma); REQUIRE_PTR(dh); REQUIRE_PTR(dx); REQUIRE_PTR(workspace);
   REQUIRE(dgamma != nullptr && rstd != nullptr, "rmsnorm_backward: dgamma or rstd is null");
   REQUIRE(dres == nullptr || aligned16(dres), "rmsnorm_backward: dres is misaligned");

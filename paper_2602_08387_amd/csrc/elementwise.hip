@@ -73,15 +73,45 @@ int launch_rmsnorm_fwd(const void* x, const void* gamma, int64_t T, int64_t D, f
 // waves through LDS and writes one fp32 partial row; a second kernel sums the partial rows.
 // ------------------------------------------------------------------------------------------
 constexpr int kRmsBwdWaves = 8;
+constexpr int kRmsBwdChunk = 4096;   // columns a wave keeps gain-gradient sums for (8 vectors of 8 per lane)
+
+// mean_d(dh * gamma * xhat) per row, for rows wider than one chunk: one wave per row at a time
+__global__ __launch_bounds__(256) void rms_dot_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
+                                                      const float* __restrict__ rstd, const bf16_t* __restrict__ dh,
+                                                      float* __restrict__ dot, int64_t T, int D) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nvec = D >> 3;
+  for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < T; row += (int64_t)gridDim.x * 4) {
+    const bf16x8* xr = reinterpret_cast<const bf16x8*>(x + row * D);
+    const bf16x8* dr = reinterpret_cast<const bf16x8*>(dh + row * D);
+    const bf16x8* gr = reinterpret_cast<const bf16x8*>(gamma);
+    const float r = rstd[row];
+    float s = 0.f;
+    for (int c = lane; c < nvec; c += 64) {
+      const bf16x8 xv = xr[c], dv = dr[c], gv = gr[c];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += (float)dv[e] * (float)gv[e] * ((float)xv[e] * r);
+    }
+    s = wave_sum(s);
+    if (lane == 0) dot[row] = s / (float)D;
+  }
+}
 
 template <int NV>
 __global__ __launch_bounds__(64 * kRmsBwdWaves) void rmsnorm_bwd_kernel(
     const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma, const float* __restrict__ rstd,
     const bf16_t* __restrict__ dh, const bf16_t* dres, bf16_t* dx, float* __restrict__ partial,
-    int64_t T, int D) {
-  extern __shared__ float red[];  // [kRmsBwdWaves][D]
+    int64_t T, int D, const float* __restrict__ dot_in) {
+  // Rows wider than 4096 are handled in column chunks of 4096, one per blockIdx.y, with the row's
+  // mean_d(dxhat * xhat) taken from dot_in (a kernel of its own computes it first); gridDim.y == 1 and
+  // dot_in == nullptr is the one-pass case.
+  extern __shared__ float red[];  // [kRmsBwdWaves][Dc]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int nvec = D >> 3;
+  const int base = blockIdx.y * kRmsBwdChunk;
+  const int Dc = gridDim.y == 1 ? D : min(kRmsBwdChunk, D - base);
+  x += base; dh += base; dx += base; gamma += base;
+  if (dres) dres += base;
+  const int nvec = Dc >> 3;
   float dg[NV][8];
   bf16x8 gv[NV];
 #pragma unroll
@@ -112,7 +142,7 @@ __global__ __launch_bounds__(64 * kRmsBwdWaves) void rmsnorm_bwd_kernel(
         }
       }
     }
-    dot = wave_sum(dot) / (float)D;
+    dot = dot_in ? dot_in[row] : wave_sum(dot) / (float)D;
     bf16x8* oxr = reinterpret_cast<bf16x8*>(dx + row * D);
     const bf16x8* rr = dres ? reinterpret_cast<const bf16x8*>(dres + row * D) : nullptr;
 #pragma unroll
@@ -137,15 +167,15 @@ __global__ __launch_bounds__(64 * kRmsBwdWaves) void rmsnorm_bwd_kernel(
     const int c = i * 64 + lane;
     if (c < nvec) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) red[wave * D + c * 8 + e] = dg[i][e];
+      for (int e = 0; e < 8; ++e) red[wave * Dc + c * 8 + e] = dg[i][e];
     }
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < D; c += blockDim.x) {
+  for (int c = threadIdx.x; c < Dc; c += blockDim.x) {
     float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < kRmsBwdWaves; ++w) s += red[w * D + c];
-    partial[(int64_t)blockIdx.x * D + c] = s;
+    for (int w = 0; w < kRmsBwdWaves; ++w) s += red[w * Dc + c];
+    partial[(int64_t)blockIdx.x * D + base + c] = s;
   }
 }
 
@@ -182,15 +212,27 @@ static int rms_bwd_blocks(int64_t T) {
   int64_t b = (T + kRmsBwdWaves - 1) / kRmsBwdWaves;
   return (int)(b < 512 ? b : 512);
 }
-size_t rmsnorm_bwd_workspace(int64_t T, int64_t D) { return (size_t)rms_bwd_blocks(T) * D * sizeof(float); }
+size_t rmsnorm_bwd_workspace(int64_t T, int64_t D) {
+  return (size_t)rms_bwd_blocks(T) * D * sizeof(float) + (D > kRmsBwdChunk ? (size_t)T * sizeof(float) : 0);
+}
 
 int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, const void* dh,
                        const void* dres, int64_t T, int64_t D, void* dx, void* dgamma,
                        int accumulate, void* workspace, hipStream_t st) {
-  const int nv = (int)((D / 8 + 63) / 64);
+  const int nchunk = (int)((D + kRmsBwdChunk - 1) / kRmsBwdChunk);
+  const int64_t Dc = nchunk == 1 ? D : kRmsBwdChunk;       // widest chunk
+  const int nv = (int)((Dc / 8 + 63) / 64);
   const int nb = rms_bwd_blocks(T);
-  const size_t lds = (size_t)kRmsBwdWaves * D * sizeof(float);
-  dim3 grid(nb), block(64 * kRmsBwdWaves);
+  const size_t lds = (size_t)kRmsBwdWaves * Dc * sizeof(float);
+  float* partial = (float*)workspace;
+  float* dot = nullptr;
+  if (nchunk > 1) {
+    dot = partial + (size_t)nb * D;
+    hipLaunchKernelGGL(rms_dot_kernel, dim3((unsigned)(T < 4096 ? (T + 3) / 4 : 1024)), dim3(256), 0, st, (const bf16_t*)x,
+                       (const bf16_t*)gamma, rstd, (const bf16_t*)dh, dot, T, (int)D);
+    if (int rc = check_launch("rmsnorm_backward(dot)")) return rc;
+  }
+  dim3 grid(nb, nchunk), block(64 * kRmsBwdWaves);
 #define RMS_BWD(NV)                                                                             \
   do {                                                                                          \
     static bool attr_set = false;                                                               \
@@ -203,13 +245,12 @@ int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, cons
     }                                                                                           \
     hipLaunchKernelGGL(rmsnorm_bwd_kernel<NV>, grid, block, lds, st, (const bf16_t*)x,          \
                        (const bf16_t*)gamma, rstd, (const bf16_t*)dh, (const bf16_t*)dres,      \
-                       (bf16_t*)dx, (float*)workspace, T, (int)D);                              \
+                       (bf16_t*)dx, partial, T, (int)D, (const float*)dot);                     \
   } while (0)
   if (nv <= 1) RMS_BWD(1);
   else if (nv <= 2) RMS_BWD(2);
   else if (nv <= 4) RMS_BWD(4);
-  else if (nv <= 8) RMS_BWD(8);
-  else return fail(-1, "rmsnorm_backward: D=%lld above 4096 is not supported", (long long)D);
+  else RMS_BWD(8);
 #undef RMS_BWD
   int rc = check_launch("rmsnorm_backward");
   if (rc) return rc;

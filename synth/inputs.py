@@ -52,6 +52,8 @@ CONFIGS = {
     "1b": LayerConfig(4, 2048, 2048, 16, 8, 128, 5632, 1e-5, 10000.0),
     "8b": LayerConfig(2, 8192, 4096, 32, 8, 128, 14336, 1e-5, 500000.0),
     "8b_stack_layer": LayerConfig(1, 8192, 4096, 32, 8, 128, 14336, 1e-5, 500000.0),
+    # not one of the five workloads: a layer twice as wide (70B-like proportions), for timing only
+    "70b_width": LayerConfig(1, 8192, 8192, 64, 8, 128, 28672, 1e-5, 500000.0),
 }
 
 WEIGHT_NAMES = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")

@@ -41,10 +41,12 @@ def test_size_queries_and_cfg_validation_on_host():
     assert expect <= got <= expect + 13 * 256
     assert K.dlayer_workspace_bytes(cfg) > 0
     for bad in (cfg.with_(head_dim=96), cfg.with_(n_kv_heads=5), cfg.with_(seq=100), cfg.with_(d_ff=1000),
-                cfg.with_(rope_layout=2), cfg.with_(batch=0), cfg.with_(d_model=8192)):
+                cfg.with_(rope_layout=2), cfg.with_(batch=0), cfg.with_(d_model=16448)):
         assert K.dlayer_saved_bytes(bad) == 0 and K.dlayer_workspace_bytes(bad) == 0
     assert K.ce_loss_workspace_bytes(8192, 128256) == 8192 * 4
     assert K.rmsnorm_backward_workspace_bytes(16384, 4096) == 512 * 4096 * 4
+    # rows wider than one 4096-column chunk also need one float per row
+    assert K.rmsnorm_backward_workspace_bytes(16384, 8192) == 512 * 8192 * 4 + 16384 * 4
 
 
 def test_product_path_does_not_import_the_oracle():

@@ -29,7 +29,8 @@ def _ws(nbytes):
 
 
 # ------------------------------------------------------------------ RMSNorm
-@pytest.mark.parametrize("T,D", [(300, 128), (1024, 768), (77, 2048), (130, 4096)])
+# rows wider than 4096 take the backward in column chunks (4096 + 1024, 2 x 4096, 4 x 4096)
+@pytest.mark.parametrize("T,D", [(300, 128), (1024, 768), (77, 2048), (130, 4096), (200, 5120), (1100, 8192), (70, 16384)])
 def test_rmsnorm_forward_backward(K, T, D):
     rng = np.random.default_rng(T + D)
     xb, gb, db, rb = (_rand_bits(rng, (T, D)), _rand_bits(rng, (D,), 0.02, 1.0),

@@ -46,8 +46,8 @@ def _oracle(cfg, inp):
     return f, r
 
 
-def _check_layer(g, f, r, tag):
-    rep = {"y": assert_close(g.y, f["y"], f"{tag}:y")}
+def _check_layer(g, f, r, tag, y_tol=REL_TOL):
+    rep = {"y": assert_close(g.y, f["y"], f"{tag}:y", rel_tol=y_tol)}
     rep["dx"] = assert_close(g.dx, r["dx"], f"{tag}:dx", rel_tol=np.inf)
     for n in si.WEIGHT_NAMES:
         rep[n] = assert_close(g.dw[n], r[n], f"{tag}:d{n}", rel_tol=np.inf)
@@ -63,6 +63,8 @@ def _check_layer(g, f, r, tag):
     # many tokens, narrow layer: every product has more tiles than workgroups and an odd number of
     # K-steps per segment (5, 5, 5 for the q/k/v input gradients, 7 + 7 for gate/up), so the
     # persistent GEMMs change their ring parity from tile to tile and across K-segments
+    # a layer wider than 4096 (70B-like proportions, few tokens)
+    ("tiny", {"seq": 256, "d_model": 8192, "n_q_heads": 8, "n_kv_heads": 2, "head_dim": 128, "d_ff": 1024}),
     ("tiny", {"batch": 16, "seq": 2048, "d_model": 320, "n_q_heads": 5, "n_kv_heads": 5, "head_dim": 64, "d_ff": 448}),
 ])
 def test_layer_matches_oracle(K, name, override):
@@ -73,7 +75,9 @@ def test_layer_matches_oracle(K, name, override):
     g.forward()
     g.backward()
     torch.cuda.synchronize()
-    rep = _check_layer(g, f, r, name)
+    # the element-wise bound on y grows with the width (see Y_TOL_8B below: rounding of the MFMA operands
+    # to bf16 alone gives 2.2e-2 at d_model 4096); at 8192 it is taken half as wide again
+    rep = _check_layer(g, f, r, name, y_tol=1.5 * Y_TOL_8B if cfg.d_model > 4096 else REL_TOL)
     print(name, override, {k: (f"{a:.2e}", f"{b:.6f}") for k, (a, b) in rep.items()})
 
 
