@@ -72,12 +72,72 @@ def cpu_baseline(cfg, budget_tokens):
                       f"({sub.tokens} of {cfg.tokens} tokens), fp64 NumPy, fwd+bwd"}
 
 
+def bench_stack(args, torch, K, si, dev_bf16):
+    """The stack workload (not the headline line): embedding -> 4 8B-shaped layers at B1 S8192 -> final
+    RMSNorm -> LM head (V = 128256) -> mean cross-entropy, and back to the embedding gradients; one step =
+    the whole forward and backward.  Pointer plumbing only; every arithmetic step is a library call."""
+    cfg, L, V = si.CONFIGS["8b_stack_layer"], 4, 128256
+    T, D = cfg.tokens, cfg.d_model
+    raw = si.make_stack_inputs(cfg, L, V, seed=0)
+    ids = torch.from_numpy(raw["ids"].reshape(-1)).cuda()
+    tgt = torch.from_numpy(raw["targets"].reshape(-1)).cuda()
+    E, w_lm, g_f = dev_bf16(raw["embed"]), dev_bf16(raw["w_lm"]), dev_bf16(raw["g_final"])
+    W = [{n: dev_bf16(w[n]) for n in si.WEIGHT_NAMES} for w in raw["layers"]]
+    del raw
+    bf = lambda *s: torch.empty(*s, dtype=torch.bfloat16, device="cuda")
+    u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device="cuda")
+    xs = [bf(T, D) for _ in range(L + 1)]
+    saved = [u8(K.dlayer_saved_bytes(cfg)) for _ in range(L)]
+    ws = u8(K.dlayer_workspace_bytes(cfg))
+    h_f, rstd_f = bf(T, D), torch.empty(T, dtype=torch.float32, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    dh_f, dw_lm, dg_f, dE = bf(T, D), bf(V, D), bf(D), bf(V, D)
+    dxa, dxb = bf(T, D), bf(T, D)
+    dW = [{n: torch.empty_like(t) for n, t in W[l].items()} for l in range(L)]
+    ws_head = u8(K.lm_head_ce_workspace_bytes(T, D, V, 0))
+    ws_norm = u8(K.rmsnorm_backward_workspace_bytes(T, D))
+
+    def step():
+        K.embed_forward(E, ids, T, V, D, xs[0])
+        for l in range(L):
+            K.dlayer_forward(cfg, xs[l], W[l], xs[l + 1], saved[l], ws)
+        K.rmsnorm_forward(xs[L], g_f, T, D, cfg.rms_eps, h_f, rstd_f)
+        K.lm_head_ce_fwd_bwd(h_f, w_lm, tgt, T, D, V, 1.0, 0, loss, dh_f, dw_lm, 0, ws_head)
+        K.rmsnorm_backward(xs[L], g_f, rstd_f, dh_f, None, T, D, dxa, dg_f, 0, ws_norm)
+        a, b = dxa, dxb
+        for l in reversed(range(L)):
+            K.dlayer_backward(cfg, xs[l], W[l], a, saved[l], b, dW[l], 0, ws)
+            a, b = b, a
+        K.embed_backward(a, ids, T, V, D, dE)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    flops = L * si.layer_fwd_bwd_flops(cfg) + 6.0 * T * D * V
+    print(json.dumps({
+        "metric": "4-layer stack fwd+bwd TFLOP/s (embedding, 4 layers, final norm, LM head, cross-entropy)",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"stack: B1 S8192, {L} x (D4096 32q/8kv x128 F14336), V {V}", "name": "stack",
+                   "tokens_per_step": T, "flops_per_step": flops},
+        "tokens_per_s": T / (ms * 1e-3), "frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "loss": float(loss.item())}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b", "70b_width"])
+    ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b", "70b_width", "stack"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=4096)
     ap.add_argument("--copy-probe", action="store_true",
@@ -96,6 +156,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.config == "stack":
+        return bench_stack(args, torch, K, si, dev_bf16)
     cfg = si.CONFIGS[args.config]
     inp = si.make_layer_inputs(cfg, seed=0)
     x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])
