@@ -120,6 +120,24 @@ def test_layer_is_causal_and_deterministic(K):
     assert not torch.equal(y1[:, t + 1:].view(torch.int16), g2.y[:, t + 1:].view(torch.int16))
 
 
+def test_layer_on_a_side_stream(K):
+    """Every call enqueues on the stream it is given: a forward + backward on a second stream (default
+    priority), with the default stream left idle, gives the bits of the default-stream run."""
+    cfg = si.CONFIGS["small"].with_(batch=2)
+    inp = si.make_layer_inputs(cfg, seed=6)
+    a = GpuLayer(K, cfg, inp)
+    a.forward(); a.backward()
+    torch.cuda.synchronize()
+    b = GpuLayer(K, cfg, inp)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        b.forward(); b.backward()
+    side.synchronize()
+    for name, p, q in [("y", a.y, b.y), ("dx", a.dx, b.dx)] + [(n, a.dw[n], b.dw[n]) for n in si.WEIGHT_NAMES]:
+        assert torch.equal(p.view(torch.int16), q.view(torch.int16)), f"{name} differs between streams"
+
+
 @pytest.mark.parametrize("name", ["tiny", "small"])
 def test_layer_replays_from_a_hip_graph(K, name):
     """The calls only enqueue kernels (no allocation, memset or synchronisation), so a forward +
