@@ -467,8 +467,9 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             // every wave now holds its last fragments of stage t in registers: refill that stage with
-            // step t+2 right away, so the loads get a whole K-step to land (measured global -> LDS
-            // latency under load: about 1800 cycles against a K-step of about 3000)
+            // step t+2 right away, so the loads get a whole K-step to land (about 2800 cycles at 1.9 GHz
+            // under sustained load; cycle counters put the wait for the slowest of them, those that
+            // miss the L2, at some 300 cycles per K-step on top of that)
             if (loader) cur.issue_next(one, st_cur, wave, tl.m0, tl.n0, lane);
             // the reads go out unconditionally (after the last K-step they fetch stale bytes nobody
             // uses), which keeps them in one block with this group's MFMAs so that the scheduler
