@@ -45,6 +45,13 @@ def test_size_queries_and_cfg_validation_on_host():
         assert K.dlayer_saved_bytes(bad) == 0 and K.dlayer_workspace_bytes(bad) == 0
     assert K.ce_loss_workspace_bytes(8192, 128256) == 8192 * 4
     assert K.rmsnorm_backward_workspace_bytes(16384, 4096) == 512 * 4096 * 4
+    # chunked LM head: one chunk of logits (1 GiB's worth of rows by default, a multiple of 256), W_lm^T, T floats
+    T, D, V = 8192, 4096, 128256
+    assert K.lm_head_ce_workspace_bytes(T, D, V, 0) == 4096 * V * 2 + V * D * 2 + T * 4
+    assert K.lm_head_ce_workspace_bytes(T, D, V, 1024) == 1024 * V * 2 + V * D * 2 + T * 4
+    assert K.lm_head_ce_workspace_bytes(512, D, V, 0) == 512 * V * 2 + V * D * 2 + 512 * 4   # fewer rows than a chunk
+    assert K.lm_head_ce_workspace_bytes(T, D, V, 100) == 0                                    # chunk not a multiple of 64
+    assert K.linear_swiglu_backward_workspace_bytes(T, D, 14336) == D * 14336 * 2
     # rows wider than one 4096-column chunk also need one float per row
     assert K.rmsnorm_backward_workspace_bytes(16384, 8192) == 512 * 8192 * 4 + 16384 * 4
 
