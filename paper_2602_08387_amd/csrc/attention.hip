@@ -516,20 +516,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-template <typename K>
-static int set_lds(K kern, size_t bytes) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e != hipSuccess) return fail(-3, "attention: cannot reserve %zu B of LDS: %s", bytes, hipGetErrorString(e));
-  return 0;
-}
-
 template <int DH>
 static int fwd_dh(const void* q, const void* k, const void* v, int64_t B, int64_t S, int64_t Hq,
                   int64_t Hkv, void* o, float* lse, hipStream_t st) {
   const size_t lds = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
-  static bool once = false;
-  if (!once) { if (int rc = set_lds(attn_fwd_kernel<DH>, lds)) return rc; once = true; }
+  static unsigned long long lds_done = 0;
+  if (int rc = reserve_lds(attn_fwd_kernel<DH>, lds, lds_done, "attention_forward")) return rc;
   const float scale_log2 = (float)(1.0 / sqrt((double)DH)) * kLog2e;
   hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((unsigned)(S / 128 * Hq * B)), dim3(256),
                      lds, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse, (int)B, (int)S,
@@ -562,13 +554,10 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
   const float scale = (float)(1.0 / sqrt((double)DH));
   const size_t lds_dq = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
   const size_t lds_kv = 2 * (2 * (size_t)RowTile<64, DH, 4>::BYTES + 512);
-  static bool once = false;
-  if (!once) {
-    if (int rc = set_lds(attn_bwd_dq_kernel<DH>, lds_dq)) return rc;
-    if (int rc = set_lds(attn_bwd_dkv_kernel<DH, true>, lds_kv)) return rc;
-    if (int rc = set_lds(attn_bwd_dkv_kernel<DH, false>, lds_kv)) return rc;
-    once = true;
-  }
+  static unsigned long long done_dq = 0, done_dv = 0, done_dk = 0;
+  if (int rc = reserve_lds(attn_bwd_dq_kernel<DH>, lds_dq, done_dq, "attention_backward")) return rc;
+  if (int rc = reserve_lds(attn_bwd_dkv_kernel<DH, true>, lds_kv, done_dv, "attention_backward")) return rc;
+  if (int rc = reserve_lds(attn_bwd_dkv_kernel<DH, false>, lds_kv, done_dk, "attention_backward")) return rc;
   const dim3 kv_grid((unsigned)(S / 128 * Hkv * B));
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, true>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
                      (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dv, (int)B, (int)S, (int)Hq,

@@ -45,4 +45,18 @@ namespace dl {
 int fail(int code, const char* fmt, ...);
 int check_launch(const char* what);
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Raises a kernel's dynamic LDS limit, once per device: the attribute belongs to the device the call is
+// made on, so a process that launches on a second GPU must set it there too.  `done` is the caller's
+// (per kernel) bit mask of devices already served.
+template <typename K>
+inline int reserve_lds(K kern, size_t bytes, unsigned long long& done, const char* what) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return fail(-3, "%s: no current device", what);
+  if ((done >> dev) & 1ull) return 0;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return fail(-3, "%s: cannot reserve %zu B of LDS: %s", what, bytes, hipGetErrorString(e));
+  done |= 1ull << dev;
+  return 0;
+}
 }  // namespace dl

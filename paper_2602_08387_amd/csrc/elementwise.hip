@@ -235,14 +235,9 @@ int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, cons
   dim3 grid(nb, nchunk), block(64 * kRmsBwdWaves);
 #define RMS_BWD(NV)                                                                             \
   do {                                                                                          \
-    static bool attr_set = false;                                                               \
-    if (!attr_set) {                                                                            \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(rmsnorm_bwd_kernel<NV>), \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,            \
-                                         kRmsBwdWaves * NV * 512 * (int)sizeof(float));         \
-      if (e != hipSuccess) return fail(-3, "rmsnorm_backward: LDS reservation failed: %s", hipGetErrorString(e)); \
-      attr_set = true;                                                                          \
-    }                                                                                           \
+    static unsigned long long lds_done = 0;                                                     \
+    if (int rc_ = reserve_lds(rmsnorm_bwd_kernel<NV>, (size_t)kRmsBwdWaves * NV * 512 * sizeof(float), lds_done,        \
+                              "rmsnorm_backward")) return rc_;                                  \
     hipLaunchKernelGGL(rmsnorm_bwd_kernel<NV>, grid, block, lds, st, (const bf16_t*)x,          \
                        (const bf16_t*)gamma, rstd, (const bf16_t*)dh, (const bf16_t*)dres,      \
                        (bf16_t*)dx, partial, T, (int)D, (const float*)dot);                     \

@@ -802,13 +802,8 @@ static int launch_group_cfg(const GemmKArgs* ks, int n, bool ak, bool bk, hipStr
 #define GEMM_GROUP_LAUNCH(AK_, BK_)                                                              \
   do {                                                                                           \
     auto kern = gemm_group_kernel<BM, BN, WM, WN, AK_, BK_>;                                     \
-    static bool attr_set = false;                                                                \
-    if (!attr_set) {                                                                             \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                    \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-      if (e != hipSuccess) return fail(-3, "gemm: cannot reserve %zu B of LDS: %s", lds, hipGetErrorString(e)); \
-      attr_set = true;                                                                           \
-    }                                                                                            \
+    static unsigned long long lds_done = 0;                                                      \
+    if (int rc_ = reserve_lds(kern, lds, lds_done, "gemm")) return rc_;                          \
     hipLaunchKernelGGL(kern, grid, block, lds, st, g);                                           \
   } while (0)
   // only the layouts in use are instantiated: the weight-gradient products (both operands mn-major)
@@ -830,13 +825,8 @@ static int launch_cfg(const GemmKArgs& k, bool ak, bool bk, hipStream_t st) {
 #define GEMM_LAUNCH(AK_, BK_)                                                                    \
   do {                                                                                           \
     auto kern = gemm_kernel<BM, BN, WM, WN, AK_, BK_>;                                           \
-    static bool attr_set = false;                                                                \
-    if (!attr_set) {                                                                             \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                    \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-      if (e != hipSuccess) return fail(-3, "gemm: cannot reserve %zu B of LDS: %s", lds, hipGetErrorString(e)); \
-      attr_set = true;                                                                           \
-    }                                                                                            \
+    static unsigned long long lds_done = 0;                                                      \
+    if (int rc_ = reserve_lds(kern, lds, lds_done, "gemm")) return rc_;                          \
     hipLaunchKernelGGL(kern, grid, block, lds, st, a);                                           \
   } while (0)
   if (ak && bk) GEMM_LAUNCH(true, true);
@@ -891,12 +881,8 @@ static int launch_fused(GemmKArgs k, const char* what, hipStream_t st) {
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
   const dim3 grid((unsigned)persistent_grid(k.tiles_m * k.tiles_n, lds)), block(WM * WN * 64);
   auto kern = gemm_swiglu_kernel<BM, BN, WM, WN, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return fail(-3, "gemm: cannot reserve %zu B of LDS: %s", lds, hipGetErrorString(e));
-    attr_set = true;
-  }
+  static unsigned long long lds_done = 0;
+  if (int rc = reserve_lds(kern, lds, lds_done, what)) return rc;
   hipLaunchKernelGGL(kern, grid, block, lds, st, k);
   return check_launch(what);
 }
