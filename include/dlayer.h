@@ -113,6 +113,20 @@ int ce_loss_fwd_bwd(const void* logits, const int64_t* targets, int64_t T, int64
                     float grad_scale, float* loss, void* dlogits, void* workspace, void* stream);
 
 /*
+ * ce_loss_fwd_bwd for callers that cannot allocate or pass scratch memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the
+ * workspace, same results bit for bit.  The per-row losses live in a static device array inside the
+ * library (CE_LOSS_STATIC_MAX_ROWS floats = 256 KiB on every GPU the library runs on, held until the
+ * process ends); T above that limit is rejected with DLAYER_ERR_INVALID.  The call allocates and
+ * frees nothing.  All calls on one GPU share that array: calls that overlap on one GPU (two streams,
+ * two threads) race and must be serialised by the caller.  The first call on a device looks up the
+ * array's address and should be made outside graph capture.
+ */
+#define CE_LOSS_STATIC_MAX_ROWS 65536
+int ce_loss_fwd_bwd_static(const void* logits, const int64_t* targets, int64_t T, int64_t V,
+                           float grad_scale, float* loss, void* dlogits, void* stream);
+
+/*
  * The LM head and its loss in one call, without ever holding all T x V logits (same training loss):
  *   logits = h w_lm^T;  loss, dlogits as in ce_loss_fwd_bwd;  dh = dlogits w_lm;  dw_lm (+)= dlogits^T h
  * The rows are walked in chunks of chunk_rows (0 = chosen by the library: about 1 GiB of logits):

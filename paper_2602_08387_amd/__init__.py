@@ -13,7 +13,7 @@ import importlib
 _BINDING_NAMES = (
     "DLayerError", "LayerCfg", "lib", "lib_path",
     "dlayer_version", "dlayer_saved_bytes", "dlayer_workspace_bytes", "dlayer_forward", "dlayer_backward",
-    "ce_loss_workspace_bytes", "ce_loss_fwd_bwd", "lm_head_ce_workspace_bytes", "lm_head_ce_fwd_bwd",
+    "ce_loss_workspace_bytes", "ce_loss_fwd_bwd", "ce_loss_fwd_bwd_static", "lm_head_ce_workspace_bytes", "lm_head_ce_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward", "rmsnorm_backward_workspace_bytes",
     "linear_forward", "linear_swiglu_forward", "linear_swiglu_backward",
     "linear_swiglu_backward_workspace_bytes", "linear_backward", "linear_backward_workspace_bytes", "linear_wgrad_group",

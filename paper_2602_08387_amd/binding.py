@@ -11,7 +11,7 @@ WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w
 
 EXPORTED_SYMBOLS = (
     "dlayer_version", "dlayer_last_error", "dlayer_saved_bytes", "dlayer_workspace_bytes",
-    "dlayer_forward", "dlayer_backward", "ce_loss_workspace_bytes", "ce_loss_fwd_bwd",
+    "dlayer_forward", "dlayer_backward", "ce_loss_workspace_bytes", "ce_loss_fwd_bwd", "ce_loss_fwd_bwd_static",
     "lm_head_ce_workspace_bytes", "lm_head_ce_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward_workspace_bytes", "rmsnorm_backward",
     "linear_forward", "linear_swiglu_forward", "linear_swiglu_backward_workspace_bytes",
@@ -64,6 +64,7 @@ def _load():
         "lm_head_ce_workspace_bytes": (sz, [i64, i64, i64, i64]),
         "lm_head_ce_fwd_bwd": (C.c_int, [vp, vp, vp, i64, i64, i64, C.c_float, i64, vp, vp, vp, C.c_int, vp, vp]),
         "ce_loss_fwd_bwd": (C.c_int, [vp, vp, i64, i64, f32, vp, vp, vp, vp]),
+        "ce_loss_fwd_bwd_static": (C.c_int, [vp, vp, i64, i64, f32, vp, vp, vp]),
         "rmsnorm_forward": (C.c_int, [vp, vp, i64, i64, f32, vp, vp, vp]),
         "rmsnorm_backward_workspace_bytes": (sz, [i64, i64]),
         "rmsnorm_backward": (C.c_int, [vp, vp, vp, vp, vp, i64, i64, vp, vp, C.c_int, vp, vp]),
@@ -160,6 +161,11 @@ def lm_head_ce_fwd_bwd(h, w_lm, targets, T, D, V, grad_scale, chunk_rows, loss, 
 def ce_loss_fwd_bwd(logits, targets, T, V, grad_scale, loss, dlogits, workspace, stream=None):
     _check(lib.ce_loss_fwd_bwd(_p(logits), _p(targets), T, V, grad_scale, _p(loss), _p(dlogits),
                                _p(workspace), _stream(stream)), "ce_loss_fwd_bwd")
+
+
+def ce_loss_fwd_bwd_static(logits, targets, T, V, grad_scale, loss, dlogits, stream=None):
+    _check(lib.ce_loss_fwd_bwd_static(_p(logits), _p(targets), T, V, grad_scale, _p(loss), _p(dlogits),
+                                      _stream(stream)), "ce_loss_fwd_bwd_static")
 
 
 def rmsnorm_forward(x, gamma, T, D, eps, h, rstd, stream=None):

@@ -319,6 +319,17 @@ int ce_loss_fwd_bwd(const void* logits, const int64_t* targets, int64_t T, int64
   return launch_ce(logits, targets, T, V, grad_scale, loss, dlogits, workspace, (hipStream_t)stream);
 }
 
+int ce_loss_fwd_bwd_static(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
+                           float* loss, void* dlogits, void* stream) {
+  REQUIRE(T > 0 && V > 0 && V % 8 == 0, "ce_loss_fwd_bwd_static: need T > 0, V > 0, V %% 8 == 0 (T=%lld V=%lld)", (long long)T, (long long)V);
+  REQUIRE(T <= ce_static_max_rows(), "ce_loss_fwd_bwd_static: T=%lld exceeds the %lld rows the static scratch holds; use ce_loss_fwd_bwd",
+          (long long)T, (long long)ce_static_max_rows());
+  REQUIRE_PTR(logits); REQUIRE_PTR(dlogits);
+  REQUIRE(targets != nullptr && loss != nullptr, "ce_loss_fwd_bwd_static: targets or loss is null");
+  TRY(check_device());
+  return launch_ce_static(logits, targets, T, V, grad_scale, loss, dlogits, (hipStream_t)stream);
+}
+
 // rows of logits held at a time by lm_head_ce_fwd_bwd
 static int64_t lm_head_chunk(int64_t T, int64_t V, int64_t chunk_rows) {
   int64_t c = chunk_rows;

@@ -8,8 +8,15 @@
 // served by the L2 and the memory-side cache, so HBM still sees 2 bytes in + 2 bytes out per logit.
 #include "common.h"
 #include "kernels.h"
+#include <atomic>
 
 namespace dl {
+
+// Per-row losses of the allocation-free entry point: one float per row, at most kCeStaticMaxRows rows
+// (256 KiB, held by every GPU the library runs on until the process ends).  In host code this name
+// is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+constexpr int64_t kCeStaticMaxRows = 65536;
+static __device__ __align__(256) float scratch[kCeStaticMaxRows];
 
 constexpr int kCeThreads = 1024;
 constexpr float kCeLog2e = 1.4426950408889634f;
@@ -170,6 +177,33 @@ int launch_ce(const void* logits, const int64_t* targets, int64_t T, int64_t V, 
   int rc = launch_ce_rows(logits, targets, T, V, grad_scale / (float)T, row_loss, dlogits, st);
   if (rc) return rc;
   return launch_ce_mean(row_loss, T, loss, st);
+}
+
+// Device address of `scratch` on the current device, looked up once per device (each GPU holds its
+// own copy of the array at its own address).
+static int ce_static_rows(float** out) {
+  static std::atomic<float*> ptrs[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return fail(-3, "ce_loss_fwd_bwd_static: no current device");
+  float* p = ptrs[dev].load(std::memory_order_acquire);
+  if (!p) {
+    hipError_t e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(-3, "ce_loss_fwd_bwd_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    ptrs[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return 0;
+}
+
+int64_t ce_static_max_rows() { return kCeStaticMaxRows; }
+
+// launch_ce with the per-row losses in the library's own static device array: every row < T is
+// written by the row kernel before the mean kernel reads it, so nothing needs clearing between calls.
+int launch_ce_static(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
+                     float* loss, void* dlogits, hipStream_t st) {
+  float* row_loss = nullptr;
+  if (int rc = ce_static_rows(&row_loss)) return rc;
+  return launch_ce(logits, targets, T, V, grad_scale, loss, dlogits, row_loss, st);
 }
 
 }  // namespace dl

@@ -93,5 +93,9 @@ int launch_ce(const void* logits, const int64_t* targets, int64_t T, int64_t V, 
 int launch_ce_rows(const void* logits, const int64_t* targets, int64_t rows, int64_t V, float scale, float* row_loss,
                    void* dlogits, hipStream_t st);
 int launch_ce_mean(const float* row_loss, int64_t T, float* loss, hipStream_t st);
+// launch_ce for at most ce_static_max_rows() rows, with the per-row losses in a static device array
+int64_t ce_static_max_rows();
+int launch_ce_static(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
+                     float* loss, void* dlogits, hipStream_t st);
 
 }  // namespace dl
