@@ -170,18 +170,31 @@ int rmsnorm_backward(const void* x, const void* gamma, const float* rstd, const 
 int linear_forward(const void* x, const void* w, const void* residual, int64_t T, int64_t K,
                    int64_t N, void* y, void* stream);
 
-/* The gated pair of the SwiGLU MLP of the transformer block (Fig. 2; Training Pipeline paragraph): g = x Wg^T, u = x Wu^T, a = silu(g) * u, the
- * activation taken from g and u as stored (rounded to bf16), so a equals swiglu_forward(g, u) bit
- * for bit.  x [T, K], w_gate and w_up [F, K], g, u, a [T, F] dense; all bf16.  K % 64 == 0,
- * F % 8 == 0.  Large problems run as one kernel whose epilogue applies the activation; small ones
- * as two products and the activation kernel.                                                   */
+/* The three head projections of the transformer block (Fig. 2; Training Pipeline paragraph) in one
+ * launch, q and k leaving it rotated: q = RoPE(h Wq^T), k = RoPE(h Wk^T), v = h Wv^T.  The rotation
+ * (dlayer_cfg: angle and the two pairings; position = token index within its batch row) is applied
+ * in the product's epilogue to the fp32 sums, so q and k are rounded to bf16 once.
+ * h [B*S, D], wq [Hq*dh, D], wk and wv [Hkv*dh, D], q [B*S, Hq*dh], k and v [B*S, Hkv*dh]; all bf16.
+ * D % 64 == 0.  workspace (device): qkv_rope_workspace_bytes(seq, head_dim), receives the fp32 cos and
+ * sin of every (position, pair), evaluated in fp64.                                              */
+size_t qkv_rope_workspace_bytes(int64_t seq, int64_t head_dim);
+int qkv_rope_forward(const void* h, const void* wq, const void* wk, const void* wv, int64_t batch,
+                     int64_t seq, int64_t d_model, int64_t n_q_heads, int64_t n_kv_heads,
+                     int64_t head_dim, float rope_base, int32_t rope_layout, void* q, void* k, void* v,
+                     void* workspace, void* stream);
+
+/* The gated pair of the SwiGLU MLP of the transformer block (Fig. 2; Training Pipeline paragraph):
+ * g = x Wg^T, u = x Wu^T, a = silu(g) * u.  x [T, K], w_gate and w_up [F, K], g, u, a [T, F] dense;
+ * all bf16.  K % 64 == 0, F % 8 == 0.  Large problems run as one kernel whose epilogue applies the
+ * activation to the fp32 sums (a is rounded once); small ones as two products and the activation
+ * kernel, which reads g and u as stored.                                                       */
 int linear_swiglu_forward(const void* x, const void* w_gate, const void* w_up, int64_t T, int64_t K,
                           int64_t F, void* g, void* u, void* a, void* stream);
 
 /* Backward of y = a W_down^T with a = silu(g) * u, as far as g and u: da = dy W_down, then
- * (dg, du) = swiglu_backward(g, u, da) for da rounded to bf16, so the result equals
- * linear_backward (dx only) followed by swiglu_backward bit for bit; large problems run as one
- * kernel that never stores da.  dy [T, D], w_down [D, F], g, u, dg, du [T, F] dense; all bf16.
+ * (dg, du) = swiglu_backward(g, u, da); large problems run as one kernel that applies the gradient to
+ * the fp32 sums of da and never stores it, small ones as the product (da rounded to bf16) and the
+ * activation-gradient kernel.  dy [T, D], w_down [D, F], g, u, dg, du [T, F] dense; all bf16.
  * T, D, F multiples of 64.  workspace (device; receives a transposed copy of w_down):
  * linear_swiglu_backward_workspace_bytes(T, D, F).                                             */
 size_t linear_swiglu_backward_workspace_bytes(int64_t T, int64_t D, int64_t F);
@@ -202,7 +215,7 @@ int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int
  * pointers; dy, x, dw, N, K are host arrays of length n.  T, N[i], K[i] multiples of 64.  The tile
  * sequences of the n products are laid end to end, so a product that leaves the last round of
  * workgroups partly filled (or is too small to fill the chip) runs alongside the next one;
- * dlayer_backward computes its seven weight gradients this way (Sec. 3.1's layer, backward).
+ * dlayer_backward computes the seven weight gradients of the transformer block (Fig. 2) this way.
  * Results are bitwise those of n linear_backward calls with dx == NULL.                      */
 int linear_wgrad_group(int32_t n, const void* const* dy, const void* const* x, const int64_t* N,
                        const int64_t* K, int64_t T, void* const* dw, int accumulate_dw, void* stream);

@@ -15,7 +15,7 @@ _BINDING_NAMES = (
     "dlayer_version", "dlayer_saved_bytes", "dlayer_workspace_bytes", "dlayer_forward", "dlayer_backward",
     "ce_loss_workspace_bytes", "ce_loss_fwd_bwd", "ce_loss_fwd_bwd_static", "lm_head_ce_workspace_bytes", "lm_head_ce_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward", "rmsnorm_backward_workspace_bytes",
-    "linear_forward", "linear_swiglu_forward", "linear_swiglu_backward",
+    "linear_forward", "qkv_rope_workspace_bytes", "qkv_rope_forward", "linear_swiglu_forward", "linear_swiglu_backward",
     "linear_swiglu_backward_workspace_bytes", "linear_backward", "linear_backward_workspace_bytes", "linear_wgrad_group",
     "rope_apply", "attention_forward", "attention_backward", "attention_backward_workspace_bytes",
     "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",

@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = (
     "dlayer_forward", "dlayer_backward", "ce_loss_workspace_bytes", "ce_loss_fwd_bwd", "ce_loss_fwd_bwd_static",
     "lm_head_ce_workspace_bytes", "lm_head_ce_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward_workspace_bytes", "rmsnorm_backward",
-    "linear_forward", "linear_swiglu_forward", "linear_swiglu_backward_workspace_bytes",
+    "linear_forward", "qkv_rope_workspace_bytes", "qkv_rope_forward", "linear_swiglu_forward", "linear_swiglu_backward_workspace_bytes",
     "linear_swiglu_backward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
     "attention_forward", "attention_backward_workspace_bytes", "attention_backward",
     "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",
@@ -69,6 +69,8 @@ def _load():
         "rmsnorm_backward_workspace_bytes": (sz, [i64, i64]),
         "rmsnorm_backward": (C.c_int, [vp, vp, vp, vp, vp, i64, i64, vp, vp, C.c_int, vp, vp]),
         "linear_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp]),
+        "qkv_rope_workspace_bytes": (sz, [i64, i64]),
+        "qkv_rope_forward": (C.c_int, [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, f32, i32, vp, vp, vp, vp, vp]),
         "linear_swiglu_forward": (C.c_int, [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]),
         "linear_swiglu_backward_workspace_bytes": (C.c_size_t, [i64, i64, i64]),
         "linear_swiglu_backward": (C.c_int, [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]),
@@ -193,6 +195,17 @@ def linear_backward_workspace_bytes(T, K, N) -> int:
 def linear_backward(x, w, dy, T, K, N, dx, dw, accumulate_dw, workspace, stream=None):
     _check(lib.linear_backward(_p(x), _p(w), _p(dy), T, K, N, _p(dx), _p(dw), int(accumulate_dw),
                                _p(workspace), _stream(stream)), "linear_backward")
+
+
+def qkv_rope_workspace_bytes(seq, head_dim) -> int:
+    return lib.qkv_rope_workspace_bytes(seq, head_dim)
+
+
+def qkv_rope_forward(h, wq, wk, wv, batch, seq, d_model, n_q_heads, n_kv_heads, head_dim, rope_base, rope_layout,
+                     q, k, v, workspace, stream=None):
+    _check(lib.qkv_rope_forward(_p(h), _p(wq), _p(wk), _p(wv), batch, seq, d_model, n_q_heads, n_kv_heads, head_dim,
+                                rope_base, rope_layout, _p(q), _p(k), _p(v), _p(workspace), _stream(stream)),
+           "qkv_rope_forward")
 
 
 def linear_swiglu_forward(x, w_gate, w_up, T, K, F, g, u, a, stream=None):

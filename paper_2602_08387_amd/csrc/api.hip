@@ -83,7 +83,7 @@ static const char* cfg_problem(const dlayer_cfg* c) {
 }
 
 struct Saved {
-  float *rstd1, *rstd2, *lse;
+  float *rstd1, *rstd2, *lse, *rope_cos, *rope_sin;
   void *h1, *q, *k, *v, *o, *y1, *h2, *g, *u, *a;
   size_t bytes;
 };
@@ -95,6 +95,8 @@ static Saved carve_saved(const dlayer_cfg* c, void* p) {
   s.rstd1 = (float*)cv.take(T * 4);
   s.rstd2 = (float*)cv.take(T * 4);
   s.lse = (float*)cv.take(T * c->n_q_heads * 4);
+  s.rope_cos = (float*)cv.take((size_t)c->seq * (c->head_dim / 2) * 4);
+  s.rope_sin = (float*)cv.take((size_t)c->seq * (c->head_dim / 2) * 4);
   s.h1 = cv.take(T * D * 2);
   s.q = cv.take(T * QD * 2);
   s.k = cv.take(T * KD * 2);
@@ -233,14 +235,15 @@ int dlayer_forward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w
   const int64_t Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, dh = cfg->head_dim, QD = Hq * dh, KD = Hkv * dh;
   Saved s = carve_saved(cfg, saved);
   TRY(launch_rmsnorm_fwd(x, w->g_attn, T, D, cfg->rms_eps, s.h1, s.rstd1, st));
+  TRY(launch_rope_table(s.rope_cos, s.rope_sin, S, dh, cfg->rope_base, st));
   {
     // q, k and v in one launch: their tile sequences run end to end (k and v alone do not fill the chip
-    // for small layers)
+    // for small layers); q and k leave the epilogue rotated, from the fp32 sums
     const GemmArgs qkv[3] = {nt_args(s.h1, D, w->wq, nullptr, T, D, QD, s.q), nt_args(s.h1, D, w->wk, nullptr, T, D, KD, s.k),
                              nt_args(s.h1, D, w->wv, nullptr, T, D, KD, s.v)};
-    TRY(launch_gemm_group(qkv, 3, st));
+    const RopeEpilogue rope = {s.rope_cos, s.rope_sin, (int)S, (int)dh, cfg->rope_layout, 0x3u};
+    TRY(launch_gemm_group_rope(qkv, 3, &rope, st));
   }
-  TRY(launch_rope_pair(s.q, s.k, B, S, Hq, Hkv, dh, cfg->rope_base, cfg->rope_layout, 0, st));
   TRY(launch_attention_fwd(s.q, s.k, s.v, B, S, Hq, Hkv, dh, s.o, s.lse, st));
   TRY(gemm_nt(s.o, QD, w->wo, x, T, QD, D, s.y1, st));
   TRY(launch_rmsnorm_fwd(s.y1, w->g_mlp, T, D, cfg->rms_eps, s.h2, s.rstd2, st));
@@ -287,8 +290,9 @@ int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* 
     const void* dys[1] = {k.dy1}; const void* ws[1] = {k.woT}; const int64_t ns[1] = {D};
     TRY(gemm_dgrad_t(1, dys, ws, ns, 0, T, QD, k.d_o, QD, st));
   }
-  TRY(launch_attention_bwd(s.q, s.k, s.v, s.o, k.d_o, s.lse, B, S, Hq, Hkv, dh, k.dq, k.dk, k.dv, k.attn_ws, st));
-  TRY(launch_rope_pair(k.dq, k.dk, B, S, Hq, Hkv, dh, cfg->rope_base, cfg->rope_layout, 1, st));
+  // dq and dk come back as gradients of the unrotated q and k (inverse rotation inside the kernels' stores)
+  TRY(launch_attention_bwd_rope(s.q, s.k, s.v, s.o, k.d_o, s.lse, B, S, Hq, Hkv, dh, k.dq, k.dk, k.dv, k.attn_ws,
+                                s.rope_cos, s.rope_sin, cfg->rope_layout, st));
   {
     const void* dys[3] = {k.dq, k.dk, k.dv}; const void* ws[3] = {k.wqT, k.wkT, k.wvT};
     const int64_t ns[3] = {QD, KD, KD};
@@ -412,6 +416,37 @@ int linear_forward(const void* x, const void* w, const void* residual, int64_t T
   REQUIRE(residual == nullptr || aligned16(residual), "linear_forward: residual is misaligned");
   TRY(check_device());
   return gemm_nt(x, K, w, residual, T, K, N, y, (hipStream_t)stream);
+}
+
+size_t qkv_rope_workspace_bytes(int64_t seq, int64_t head_dim) {
+  if (seq <= 0 || (head_dim != 32 && head_dim != 64 && head_dim != 128)) return 0;
+  return 2 * up256((size_t)seq * (head_dim / 2) * 4);   // cos and sin tables
+}
+
+int qkv_rope_forward(const void* h, const void* wq, const void* wk, const void* wv, int64_t batch, int64_t seq,
+                     int64_t d_model, int64_t n_q_heads, int64_t n_kv_heads, int64_t head_dim, float rope_base,
+                     int32_t rope_layout, void* q, void* k, void* v, void* workspace, void* stream) {
+  REQUIRE(batch > 0 && seq > 0 && d_model > 0 && n_q_heads > 0 && n_kv_heads > 0, "qkv_rope_forward: non-positive dimension");
+  REQUIRE(head_dim == 32 || head_dim == 64 || head_dim == 128, "qkv_rope_forward: head_dim must be 32, 64 or 128");
+  REQUIRE(d_model % 64 == 0, "qkv_rope_forward: d_model must be a multiple of 64");
+  REQUIRE(rope_layout == 0 || rope_layout == 1, "qkv_rope_forward: rope_layout must be 0 or 1");
+  REQUIRE(rope_base > 0.f, "qkv_rope_forward: rope_base must be positive");
+  const int64_t T = batch * seq, QD = n_q_heads * head_dim, KD = n_kv_heads * head_dim;
+  REQUIRE(T * d_model * 2 < ((int64_t)1 << 32) && QD * d_model * 2 < ((int64_t)1 << 32) && T * QD * 2 < ((int64_t)1 << 32) &&
+              KD * d_model * 2 < ((int64_t)1 << 32) && T * KD * 2 < ((int64_t)1 << 32),
+          "qkv_rope_forward: an operand reaches 4 GiB");
+  REQUIRE_PTR(h); REQUIRE_PTR(wq); REQUIRE_PTR(wk); REQUIRE_PTR(wv); REQUIRE_PTR(q); REQUIRE_PTR(k); REQUIRE_PTR(v);
+  REQUIRE_PTR(workspace);
+  TRY(check_device());
+  hipStream_t st = (hipStream_t)stream;
+  Carver cv(workspace);
+  float* cs = (float*)cv.take((size_t)seq * (head_dim / 2) * 4);
+  float* sn = (float*)cv.take((size_t)seq * (head_dim / 2) * 4);
+  TRY(launch_rope_table(cs, sn, seq, head_dim, rope_base, st));
+  const GemmArgs qkv[3] = {nt_args(h, d_model, wq, nullptr, T, d_model, QD, q), nt_args(h, d_model, wk, nullptr, T, d_model, KD, k),
+                           nt_args(h, d_model, wv, nullptr, T, d_model, KD, v)};
+  const RopeEpilogue rope = {cs, sn, (int)seq, (int)head_dim, rope_layout, 0x3u};
+  return launch_gemm_group_rope(qkv, 3, &rope, st);
 }
 
 int linear_swiglu_forward(const void* x, const void* w_gate, const void* w_up, int64_t T, int64_t K, int64_t F,

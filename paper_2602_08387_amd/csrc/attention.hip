@@ -280,6 +280,46 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restric
   }
 }
 
+// Rotary embedding backward on an accumulator tile held as "lane owns one token, features along
+// registers" (register g*4+e of block t2 = feature t2*32 + g*8 + 4*half + e): the gradient of a rotation
+// by angle phi is the rotation by -phi.  cr, sr: this token's cos / sin row ([DH/2] fp32).  Both
+// members of a pair sit in the same lane for either pairing.
+template <int DH>
+__device__ __forceinline__ void rope_unrotate(f32x16 (&acc)[DH / 32], const float* cr, const float* sr, int layout,
+                                              int half) {
+  if (layout == 0) {
+    constexpr int NT2 = DH >= 64 ? DH / 64 : 1, NG = DH >= 64 ? 4 : 2;
+#pragma unroll
+    for (int t2 = 0; t2 < NT2; ++t2)
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const int t2p = DH >= 64 ? t2 + DH / 64 : 0, gp = DH >= 64 ? g : g + 2;
+        const int idx = t2 * 32 + g * 8 + half * 4;
+        const f32x4 c4 = *reinterpret_cast<const f32x4*>(cr + idx), s4 = *reinterpret_cast<const f32x4*>(sr + idx);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float a = acc[t2][g * 4 + e], b = acc[t2p][gp * 4 + e];
+          acc[t2][g * 4 + e] = a * c4[e] + b * s4[e];
+          acc[t2p][gp * 4 + e] = b * c4[e] - a * s4[e];
+        }
+      }
+  } else {
+#pragma unroll
+    for (int t2 = 0; t2 < DH / 32; ++t2)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int idx = (t2 * 32 + g * 8 + half * 4) >> 1;
+        const f32x2 c2 = *reinterpret_cast<const f32x2*>(cr + idx), s2 = *reinterpret_cast<const f32x2*>(sr + idx);
+#pragma unroll
+        for (int e = 0; e < 4; e += 2) {
+          const float a = acc[t2][g * 4 + e], b = acc[t2][g * 4 + e + 1];
+          acc[t2][g * 4 + e] = a * c2[e >> 1] + b * s2[e >> 1];
+          acc[t2][g * 4 + e + 1] = b * c2[e >> 1] - a * s2[e >> 1];
+        }
+      }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // dQ.  Same decomposition as the forward: workgroup = 128 query rows of one (batch, head).
 // ------------------------------------------------------------------------------------------
@@ -287,7 +327,8 @@ template <int DH>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta,
-    bf16_t* __restrict__ dq, int B, int S, int Hq, int Hkv, float scale) {
+    bf16_t* __restrict__ dq, int B, int S, int Hq, int Hkv, float scale, const float* __restrict__ rope_cos,
+    const float* __restrict__ rope_sin, int rope_layout) {
   using Tile = RowTile<64, DH, 4>;
   constexpr int STAGE = 2 * Tile::BYTES;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -366,6 +407,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     __syncthreads();
     stage ^= 1;
   }
+  // q was rotated after its projection: hand back the gradient of the unrotated q
+  if (rope_cos) rope_unrotate<DH>(acc, rope_cos + (int64_t)(qw + lq) * (DH / 2), rope_sin + (int64_t)(qw + lq) * (DH / 2), rope_layout, half);
   bf16_t* op = dq + ((int64_t)b * S + qw + lq) * ldq + (int64_t)h * DH + half * 4;
 #pragma unroll
   for (int t2 = 0; t2 < DH / 32; ++t2)
@@ -390,7 +433,8 @@ template <int DH, bool WANT_DV>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ d_o, const float* __restrict__ lse2, const float* __restrict__ delta,
-    bf16_t* __restrict__ dout, int B, int S, int Hq, int Hkv, float scale) {
+    bf16_t* __restrict__ dout, int B, int S, int Hq, int Hkv, float scale, const float* __restrict__ rope_cos,
+    const float* __restrict__ rope_sin, int rope_layout) {
   using Tile = RowTile<64, DH, 4>;
   constexpr int STAGE = 2 * Tile::BYTES + 512;  // Q tile, dO tile, lse[64], delta[64]
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -503,6 +547,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     stage ^= 1;
   }
   const float oscale = WANT_DV ? 1.0f : scale;
+  if constexpr (!WANT_DV) {
+    if (rope_cos) rope_unrotate<DH>(acc, rope_cos + (int64_t)(kvw + lk) * (DH / 2), rope_sin + (int64_t)(kvw + lk) * (DH / 2), rope_layout, half);
+  }
   const int64_t off = ((int64_t)b * S + kvw + lk) * ldk + (int64_t)hk * DH + half * 4;
 #pragma unroll
   for (int t2 = 0; t2 < DH / 32; ++t2)
@@ -520,7 +567,7 @@ template <int DH>
 static int fwd_dh(const void* q, const void* k, const void* v, int64_t B, int64_t S, int64_t Hq,
                   int64_t Hkv, void* o, float* lse, hipStream_t st) {
   const size_t lds = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
-  static unsigned long long lds_done = 0;
+  static std::atomic<unsigned long long> lds_done{0};
   if (int rc = reserve_lds(attn_fwd_kernel<DH>, lds, lds_done, "attention_forward")) return rc;
   const float scale_log2 = (float)(1.0 / sqrt((double)DH)) * kLog2e;
   hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((unsigned)(S / 128 * Hq * B)), dim3(256),
@@ -543,7 +590,8 @@ size_t attention_bwd_workspace(int64_t B, int64_t S, int64_t Hq, int64_t, int64_
 template <int DH>
 static int bwd_dh(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                   const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, void* dq, void* dk,
-                  void* dv, void* workspace, hipStream_t st) {
+                  void* dv, void* workspace, const float* rope_cos, const float* rope_sin, int rope_layout,
+                  hipStream_t st) {
   float* delta = (float*)workspace;
   float* lse2 = delta + B * Hq * S;
   const int64_t rows = B * S * Hq;
@@ -554,31 +602,38 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
   const float scale = (float)(1.0 / sqrt((double)DH));
   const size_t lds_dq = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
   const size_t lds_kv = 2 * (2 * (size_t)RowTile<64, DH, 4>::BYTES + 512);
-  static unsigned long long done_dq = 0, done_dv = 0, done_dk = 0;
+  static std::atomic<unsigned long long> done_dq{0}, done_dv{0}, done_dk{0};
   if (int rc = reserve_lds(attn_bwd_dq_kernel<DH>, lds_dq, done_dq, "attention_backward")) return rc;
   if (int rc = reserve_lds(attn_bwd_dkv_kernel<DH, true>, lds_kv, done_dv, "attention_backward")) return rc;
   if (int rc = reserve_lds(attn_bwd_dkv_kernel<DH, false>, lds_kv, done_dk, "attention_backward")) return rc;
   const dim3 kv_grid((unsigned)(S / 128 * Hkv * B));
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, true>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
                      (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dv, (int)B, (int)S, (int)Hq,
-                     (int)Hkv, scale);
+                     (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
   if (int rc = check_launch("attention_backward(dv)")) return rc;
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, false>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
                      (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (int)B, (int)S, (int)Hq,
-                     (int)Hkv, scale);
+                     (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
   if (int rc = check_launch("attention_backward(dk)")) return rc;
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3((unsigned)(S / 128 * Hq * B)), dim3(256),
                      lds_dq, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)d_o, lse,
-                     (const float*)delta, (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale);
+                     (const float*)delta, (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
   return check_launch("attention_backward(dq)");
 }
 
 int launch_attention_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                          const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t dh,
                          void* dq, void* dk, void* dv, void* workspace, hipStream_t st) {
-  if (dh == 128) return bwd_dh<128>(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dq, dk, dv, workspace, st);
-  if (dh == 64) return bwd_dh<64>(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dq, dk, dv, workspace, st);
-  return bwd_dh<32>(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dq, dk, dv, workspace, st);
+  return launch_attention_bwd_rope(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dh, dq, dk, dv, workspace, nullptr, nullptr, 0, st);
+}
+
+int launch_attention_bwd_rope(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                              const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t dh,
+                              void* dq, void* dk, void* dv, void* workspace, const float* rope_cos,
+                              const float* rope_sin, int rope_layout, hipStream_t st) {
+  if (dh == 128) return bwd_dh<128>(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dq, dk, dv, workspace, rope_cos, rope_sin, rope_layout, st);
+  if (dh == 64) return bwd_dh<64>(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dq, dk, dv, workspace, rope_cos, rope_sin, rope_layout, st);
+  return bwd_dh<32>(q, k, v, o, d_o, lse, B, S, Hq, Hkv, dq, dk, dv, workspace, rope_cos, rope_sin, rope_layout, st);
 }
 
 }  // namespace dl

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -48,15 +49,16 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // Raises a kernel's dynamic LDS limit, once per device: the attribute belongs to the device the call is
 // made on, so a process that launches on a second GPU must set it there too.  `done` is the caller's
-// (per kernel) bit mask of devices already served.
+// (per kernel) bit mask of devices already served; threads may race to set the attribute (setting it
+// twice is harmless), never on the mask.
 template <typename K>
-inline int reserve_lds(K kern, size_t bytes, unsigned long long& done, const char* what) {
+inline int reserve_lds(K kern, size_t bytes, std::atomic<unsigned long long>& done, const char* what) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return fail(-3, "%s: no current device", what);
-  if ((done >> dev) & 1ull) return 0;
+  if ((done.load(std::memory_order_acquire) >> dev) & 1ull) return 0;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
   if (e != hipSuccess) return fail(-3, "%s: cannot reserve %zu B of LDS: %s", what, bytes, hipGetErrorString(e));
-  done |= 1ull << dev;
+  done.fetch_or(1ull << dev, std::memory_order_release);
   return 0;
 }
 }  // namespace dl

@@ -235,7 +235,7 @@ int launch_rmsnorm_bwd(const void* x, const void* gamma, const float* rstd, cons
   dim3 grid(nb, nchunk), block(64 * kRmsBwdWaves);
 #define RMS_BWD(NV)                                                                             \
   do {                                                                                          \
-    static unsigned long long lds_done = 0;                                                     \
+    static std::atomic<unsigned long long> lds_done{0};                                                     \
     if (int rc_ = reserve_lds(rmsnorm_bwd_kernel<NV>, (size_t)kRmsBwdWaves * NV * 512 * sizeof(float), lds_done,        \
                               "rmsnorm_backward")) return rc_;                                  \
     hipLaunchKernelGGL(rmsnorm_bwd_kernel<NV>, grid, block, lds, st, (const bf16_t*)x,          \
@@ -331,6 +331,27 @@ int launch_rope_pair(void* q, void* k, int64_t batch, int64_t seq, int64_t n_q_h
   hipLaunchKernelGGL(rope_kernel, dim3((unsigned)(batch * seq)), dim3(256), 0, st, (bf16_t*)q, (bf16_t*)k, (int)seq,
                      (int)n_q_heads, (int)n_kv_heads, (int)head_dim, log2((double)base), layout, inverse);
   return check_launch("rope_apply(q, k)");
+}
+
+// The angles as a table for the kernels that rotate inside another pass (the q/k projection epilogue,
+// the attention backward stores): one thread per (position, pair).
+__global__ __launch_bounds__(256) void rope_table_kernel(float* __restrict__ cs, float* __restrict__ sn, int seq, int half,
+                                                         double log2_base) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= seq * half) return;
+  const int p = idx / half, i = idx % half;
+  const double theta = exp2(-(double)i / (double)half * log2_base);
+  double s, c;
+  sincos((double)p * theta, &s, &c);
+  cs[idx] = (float)c;
+  sn[idx] = (float)s;
+}
+
+int launch_rope_table(float* cos, float* sin, int64_t seq, int64_t head_dim, float base, hipStream_t st) {
+  const int64_t n = seq * (head_dim / 2);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, cos, sin, (int)seq,
+                     (int)(head_dim / 2), log2((double)base));
+  return check_launch("rope table");
 }
 
 // ------------------------------------------------------------------------------------------

@@ -25,6 +25,7 @@
 // rows of C.
 #include "common.h"
 #include "kernels.h"
+#include <atomic>
 #include <type_traits>
 
 namespace dl {
@@ -65,6 +66,8 @@ struct GemmKArgs {
   // activation-gradient epilogue only (see EPI_SWIGLU_GRAD)
   const bf16_t *e1, *e2;
   int64_t lde;
+  // rotary epilogue only (see EPI_ROPE): rotate this problem's output
+  int rope;
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
@@ -127,6 +130,24 @@ struct TileLoader {
       if constexpr (KMAJOR) vo = voff[i % NVAR];
       else vo = voff[0] + (uint32_t)((pc ^ mn_swz(j * RPI + kq)) << 4);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, vo, soff, 0, 0);
+    }
+  }
+  // Tile of a k-major matrix whose rows are heads of 128 features, loaded so that a wave whose MFMA
+  // tile spans 64 tile rows holds 32 features of a head's first half and, 32 tile rows further, their
+  // rotary partners 64 features on: tile row r <- matrix row
+  // 128 * (r / 128) + 32 * ((r / 64) & 1) + r % 32 + 64 * ((r / 32) & 1).
+  static __device__ __forceinline__ int perm_row(int r) {
+    return ((r >> 7) << 7) + (((r >> 6) & 1) << 5) + (r & 31) + (((r >> 5) & 1) << 6);
+  }
+  template <int I0, int I1>
+  __device__ __forceinline__ void issue_perm_range(__amdgpu_buffer_rsrc_t rs, char* lds_tile, int wave, int64_t ld,
+                                                   int k0) const {
+    static_assert(KMAJOR && 32 % RPI == 0, "an instruction's rows must lie in one run of 32");
+#pragma unroll
+    for (int i = I0; i < I1; ++i) {
+      const int j = wave * PER_WAVE + i;
+      const uint32_t soff = (uint32_t)(((int64_t)perm_row(j * RPI) * ld + k0) * 2);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, voff[i % NVAR], soff, 0, 0);
     }
   }
   // Tile of a PAIR of k-major matrices: of every 64 tile rows the first 32 are rows of the first
@@ -211,7 +232,8 @@ __device__ __forceinline__ void wait_frags(bf16x8 (&fa)[FM], bf16x8 (&fb)[FN]) {
 // Position of the next tile pair to fetch: segment, k offset, and that segment's descriptors.
 // PAIR: the B tile interleaves two weight matrices (TileLoader::issue_pair_range); n0 and N then
 // count columns of the interleaved product, twice the rows of either matrix.
-template <int BM, int BN, int NW, bool AK, bool BKM, bool PAIR = false>
+// PERM: the B tile takes its rows in the rotary-partner order of TileLoader::issue_perm_range.
+template <int BM, int BN, int NW, bool AK, bool BKM, bool PAIR = false, bool PERM = false>
 struct LoadCursor {
   TileLoader<BM, AK, NW> la;
   TileLoader<BN, BKM, NW> lb;
@@ -253,6 +275,8 @@ struct LoadCursor {
       la.template issue_range<C * PA / NC, (C + 1) * PA / NC>(ra, stage, wave, lda, k);
       if constexpr (PAIR)
         lb.template issue_pair_range<C * PB / NC, (C + 1) * PB / NC>(rb, rb2, stage + BM * BK * 2, wave, ldb, k);
+      else if constexpr (PERM)
+        lb.template issue_perm_range<C * PB / NC, (C + 1) * PB / NC>(rb, stage + BM * BK * 2, wave, ldb, k);
       else
         lb.template issue_range<C * PB / NC, (C + 1) * PB / NC>(rb, stage + BM * BK * 2, wave, ldb, k);
       if constexpr (C + 1 == NC) {
@@ -270,6 +294,8 @@ struct LoadCursor {
       la.issue(ra, stage, wave, lda, k);
       if constexpr (PAIR)
         lb.template issue_pair_range<0, TileLoader<BN, BKM, NW>::PER_WAVE>(rb, rb2, stage + BM * BK * 2, wave, ldb, k);
+      else if constexpr (PERM)
+        lb.template issue_perm_range<0, TileLoader<BN, BKM, NW>::PER_WAVE>(rb, stage + BM * BK * 2, wave, ldb, k);
       else
         lb.issue(rb, stage + BM * BK * 2, wave, ldb, k);
       k += BK;
@@ -295,6 +321,9 @@ struct GemmGroupKArgs {
   GemmKArgs prob[MAX_GROUP];
   int tile_start[MAX_GROUP + 1];
   int n;
+  // rotary epilogue only (see EPI_ROPE): cos and sin of the angle of (position, pair), [seq][head_dim/2]
+  const float *rope_cos, *rope_sin;
+  int rope_seq, rope_dh, rope_layout;
 };
 
 // Persistent workgroup: one per CU, walking the tile sequence with stride gridDim.x.  Between two
@@ -314,8 +343,16 @@ struct GemmGroupKArgs {
 // EPI_SWIGLU_GRAD: the product is da, the gradient arriving at a = silu(g) * u; the epilogue reads the
 // g and u tiles (e1, e2, leading dimension lde) and stores dg to c and du to c2 instead of da,
 // again from the rounded da like the separate kernel.
-enum { EPI_PLAIN = 0, EPI_SWIGLU = 1, EPI_SWIGLU_GRAD = 2 };
-template <bool GROUPED, int BM, int BN, int WM, int WN, bool AK, bool BKM, int EPI = EPI_PLAIN>
+//
+// EPI_ROPE (grouped launch of head projections): problems flagged `rope` have the rotary embedding
+// applied to their output in the epilogue, on the fp32 accumulators, so that q and k are rounded to
+// bf16 once.  Rows of C are tokens (position = row % rope_seq), columns are [head][head_dim].  A wave
+// owns 64 columns and needs both members of a pair: with adjacent pairs (2i, 2i+1) a lane holds them
+// already; with split pairs (i, i + head_dim/2) a 64-wide head is one wave's strip, a 32-wide head half
+// of one, and for 128-wide heads the B tile is loaded in partner order (PERM, every problem of the
+// launch) and the epilogue stores the two 32-column runs of a wave where they belong.
+enum { EPI_PLAIN = 0, EPI_SWIGLU = 1, EPI_SWIGLU_GRAD = 2, EPI_ROPE = 3 };
+template <bool GROUPED, int BM, int BN, int WM, int WN, bool AK, bool BKM, int EPI = EPI_PLAIN, bool PERM = false>
 __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const GemmKArgs& one) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM, TN = BN / WN;
@@ -348,10 +385,12 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
 
   // What the epilogue needs of a tile's problem, by value (the next tile's cursor is opened before the
   // current tile's epilogue runs).
-  struct Tile { int m0, n0, total, M, N, accumulate; bf16_t* c; const bf16_t* r; int64_t ldc; };
+  struct Tile { int m0, n0, total, M, N, accumulate, rope; bf16_t* c; const bf16_t* r; int64_t ldc; };
   constexpr bool SWIGLU = EPI == EPI_SWIGLU;
-  LoadCursor<BM, BN, NL, AK, BKM, SWIGLU> cur;
-  static_assert(EPI == EPI_PLAIN || (!GROUPED && TN == 64 && MI == 16), "fused epilogues: one 64-column strip per wave");
+  LoadCursor<BM, BN, NL, AK, BKM, SWIGLU, PERM> cur;
+  static_assert(EPI == EPI_PLAIN || (TN == 64 && MI == 16), "fused epilogues: one 64-column strip per wave");
+  static_assert(EPI == EPI_PLAIN || GROUPED == (EPI == EPI_ROPE), "the rotary epilogue is the grouped launch's, the others are not");
+  static_assert(!PERM || (EPI == EPI_ROPE && AK && BKM && BN % 128 == 0), "partner-order tiles: rotary epilogue only");
 
   // tile id -> tile origin, and the load cursor opened on the tile's first K-segment.  The tile
   // sequence of a problem runs in bands of 8 tile-rows, so that the ~32 consecutive tiles an XCD holds
@@ -366,6 +405,7 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
       tiles_m = q.tiles_m; tiles_n = q.tiles_n; K0 = q.K[0];
       a0 = q.a[0]; b0 = q.b[0]; lda0 = q.lda[0]; ldb0 = q.ldb[0];
       t.M = q.M; t.N = q.N; t.accumulate = q.accumulate; t.c = q.c; t.r = q.r; t.ldc = q.ldc;
+      t.rope = EPI == EPI_ROPE ? q.rope : 0;
     };
     if constexpr (GROUPED) {
       // problem index: the number of problems whose first tile is not after pid
@@ -629,7 +669,7 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
         for (int i = 0; i < TPB; ++i)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float z = (float)gq[i][e], d = (float)(bf16_t)acc[i][s][e];
+            const float z = (float)gq[i][e], d = acc[i][s][e];
             const float sg = 1.0f / (1.0f + __expf(-z));
             gq[i][e] = (bf16_t)(d * (float)uq[i][e] * sg * (1.0f + z * (1.0f - sg)));
             uq[i][e] = (bf16_t)(d * z * sg);
@@ -675,8 +715,8 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
             bf16x4 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const float z = (float)(bf16_t)acc[i][hf * HF + jj][e];
-              o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * (float)(bf16_t)acc[i + 2][hf * HF + jj][e]);
+              const float z = acc[i][hf * HF + jj][e];
+              o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * acc[i + 2][hf * HF + jj][e]);
             }
             *reinterpret_cast<bf16x4*>(stg + stg_off(jj, i, 0)) = o;
           }
@@ -719,6 +759,51 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
                 for (int e = 0; e < 4; ++e) acc[nb * TPB + i][hf * HF + jj][g * 4 + e] += (float)v[e];
               }
         }
+        if constexpr (EPI == EPI_ROPE) {
+          if (p.rope) {
+            const int hd2 = grp.rope_dh >> 1;
+#pragma unroll
+            for (int jj = 0; jj < HF; ++jj) {
+              const int j = hf * HF + jj;
+              const int pos = (mbase + jj * MI + lm) % grp.rope_seq;
+              const float* cr = grp.rope_cos + (int64_t)pos * hd2;
+              const float* sr = grp.rope_sin + (int64_t)pos * hd2;
+              if (grp.rope_layout == 0) {
+                // block ib holds first-half features idx .. idx+3 of a head for this lane, block pb their partners
+                const bool narrow = grp.rope_dh == 32;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                  const int idx = narrow ? lq * 4 : (PERM ? (wave_n & 1) * 32 : 0) + t * 16 + lq * 4;
+                  const f32x4 c4 = *reinterpret_cast<const f32x4*>(cr + idx);
+                  const f32x4 s4 = *reinterpret_cast<const f32x4*>(sr + idx);
+                  auto rot = [&](acc_t& a, acc_t& b) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                      const float fa = a[e], fb = b[e];
+                      a[e] = fa * c4[e] - fb * s4[e];
+                      b[e] = fa * s4[e] + fb * c4[e];
+                    }
+                  };
+                  if (narrow) rot(acc[2 * t][j], acc[2 * t + 1][j]);
+                  else rot(acc[t][j], acc[t + 2][j]);
+                }
+              } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                  const int idx = ((nbase + i * MI + lq * 4) % grp.rope_dh) >> 1;
+                  const f32x2 c2 = *reinterpret_cast<const f32x2*>(cr + idx);
+                  const f32x2 s2 = *reinterpret_cast<const f32x2*>(sr + idx);
+#pragma unroll
+                  for (int e = 0; e < 4; e += 2) {
+                    const float fa = acc[i][j][e], fb = acc[i][j][e + 1];
+                    acc[i][j][e] = fa * c2[e >> 1] - fb * s2[e >> 1];
+                    acc[i][j][e + 1] = fa * s2[e >> 1] + fb * c2[e >> 1];
+                  }
+                }
+              }
+            }
+          }
+        }
 #pragma unroll
         for (int jj = 0; jj < HF; ++jj)
 #pragma unroll
@@ -740,7 +825,10 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
         for (int t = 0; t < HM / 8; ++t) {
           const int row = t * 8 + rrow;
           const int m = mbase + row;
-          const int n = nbase + ((rpc ^ ((row >> 1) & 7)) << 3);
+          const int cl = (rpc ^ ((row >> 1) & 7)) << 3;   // column among the wave's 64
+          // partner-order tiles: staged columns 0..31 are features (wave_n & 1) * 32 + .. of head wave_n / 2 of
+          // the tile, columns 32..63 the same features 64 further on
+          const int n = PERM ? n0 + (wave_n >> 1) * 128 + (wave_n & 1) * 32 + (cl & 31) + ((cl >> 5) << 6) : nbase + cl;
           const bf16x8 v = *reinterpret_cast<const bf16x8*>(stg + row * 128 + (rpc << 4));
           if (m < p.M && n < p.N) *reinterpret_cast<bf16x8*>(p.c + (int64_t)m * p.ldc + n) = v;
         }
@@ -766,16 +854,24 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_group_kernel(const GemmGroup
   gemm_persistent<true, BM, BN, WM, WN, AK, BKM>(g, g.prob[0]);
 }
 
+template <int BM, int BN, int WM, int WN, bool PERM>
+__global__ __launch_bounds__(WM* WN * 64, WM* WN == 4 ? 2 : 1) void gemm_group_rope_kernel(const GemmGroupKArgs g) {
+  gemm_persistent<true, BM, BN, WM, WN, true, true, EPI_ROPE, PERM>(g, g.prob[0]);
+}
+
 // As many workgroups as the LDS lets a CU hold at once (one for the 256 x 256 tile's 160 KB, two for
 // the 128 x 128 tile's 72 KB, which then also gives every SIMD a second wave), fewer if there are fewer
 // tiles.
 static int persistent_grid(int ntiles, size_t lds) {
-  static int cus = 0;
+  static std::atomic<int> cu_count[64];   // per device; 0 = not asked yet
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return ntiles;
+  int cus = cu_count[dev].load(std::memory_order_relaxed);
   if (cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return ntiles;
-    cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return ntiles;
+    cus = n > 0 ? n : 256;
+    cu_count[dev].store(cus, std::memory_order_relaxed);
   }
   const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
   return ntiles < cus * per_cu ? ntiles : cus * per_cu;
@@ -788,7 +884,7 @@ static size_t lds_bytes(int nwaves, int wm) {
 }
 
 template <int BM, int BN, int WM, int WN>
-static int launch_group_cfg(const GemmKArgs* ks, int n, bool ak, bool bk, hipStream_t st) {
+static int launch_group_cfg(const GemmKArgs* ks, int n, bool ak, bool bk, const RopeEpilogue* rope, hipStream_t st) {
   GemmGroupKArgs g{};
   g.n = n;
   for (int i = 0; i < n; ++i) {
@@ -799,10 +895,26 @@ static int launch_group_cfg(const GemmKArgs* ks, int n, bool ak, bool bk, hipStr
   }
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
   const dim3 grid((unsigned)persistent_grid(g.tile_start[n], lds)), block(WM * WN * 64);
+  if (rope) {
+    g.rope_cos = rope->cos; g.rope_sin = rope->sin;
+    g.rope_seq = rope->seq; g.rope_dh = rope->head_dim; g.rope_layout = rope->layout;
+    for (int i = 0; i < n; ++i) g.prob[i].rope = (rope->rotate_mask >> i) & 1;
+#define GEMM_ROPE_LAUNCH(PERM_)                                                                  \
+  do {                                                                                           \
+    auto kern = gemm_group_rope_kernel<BM, BN, WM, WN, PERM_>;                                   \
+    static std::atomic<unsigned long long> lds_done{0};                                          \
+    if (int rc_ = reserve_lds(kern, lds, lds_done, "gemm rope")) return rc_;                     \
+    hipLaunchKernelGGL(kern, grid, block, lds, st, g);                                           \
+  } while (0)
+    if (rope->layout == 0 && rope->head_dim == 128) GEMM_ROPE_LAUNCH(true);
+    else GEMM_ROPE_LAUNCH(false);
+#undef GEMM_ROPE_LAUNCH
+    return check_launch("gemm group (rotary epilogue)");
+  }
 #define GEMM_GROUP_LAUNCH(AK_, BK_)                                                              \
   do {                                                                                           \
     auto kern = gemm_group_kernel<BM, BN, WM, WN, AK_, BK_>;                                     \
-    static unsigned long long lds_done = 0;                                                      \
+    static std::atomic<unsigned long long> lds_done{0};                                                      \
     if (int rc_ = reserve_lds(kern, lds, lds_done, "gemm")) return rc_;                          \
     hipLaunchKernelGGL(kern, grid, block, lds, st, g);                                           \
   } while (0)
@@ -825,7 +937,7 @@ static int launch_cfg(const GemmKArgs& k, bool ak, bool bk, hipStream_t st) {
 #define GEMM_LAUNCH(AK_, BK_)                                                                    \
   do {                                                                                           \
     auto kern = gemm_kernel<BM, BN, WM, WN, AK_, BK_>;                                           \
-    static unsigned long long lds_done = 0;                                                      \
+    static std::atomic<unsigned long long> lds_done{0};                                                      \
     if (int rc_ = reserve_lds(kern, lds, lds_done, "gemm")) return rc_;                          \
     hipLaunchKernelGGL(kern, grid, block, lds, st, a);                                           \
   } while (0)
@@ -881,7 +993,7 @@ static int launch_fused(GemmKArgs k, const char* what, hipStream_t st) {
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
   const dim3 grid((unsigned)persistent_grid(k.tiles_m * k.tiles_n, lds)), block(WM * WN * 64);
   auto kern = gemm_swiglu_kernel<BM, BN, WM, WN, EPI>;
-  static unsigned long long lds_done = 0;
+  static std::atomic<unsigned long long> lds_done{0};
   if (int rc = reserve_lds(kern, lds, lds_done, what)) return rc;
   hipLaunchKernelGGL(kern, grid, block, lds, st, k);
   return check_launch(what);
@@ -928,7 +1040,9 @@ int launch_gemm_swiglu_grad(const void* dy, int64_t lddy, const void* wt, int64_
   return launch_fused<EPI_SWIGLU_GRAD>(k, "gemm swiglu grad", st);
 }
 
-int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st) {
+int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st) { return launch_gemm_group_rope(gs, n, nullptr, st); }
+
+int launch_gemm_group_rope(const GemmArgs* gs, int n, const RopeEpilogue* rope, hipStream_t st) {
   if (n < 1 || n > MAX_GROUP) return fail(-1, "gemm group: 1..%d problems, got %d", MAX_GROUP, n);
   GemmKArgs ks[MAX_GROUP];
   int64_t tiles256 = 0;
@@ -939,8 +1053,15 @@ int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st) {
     ks[i] = kernel_args(gs[i]);
     tiles256 += (int64_t)((gs[i].M + 255) / 256) * ((gs[i].N + 255) / 256);
   }
-  if (tiles256 >= 192) return launch_group_cfg<256, 256, 2, 4>(ks, n, gs[0].a_kmajor, gs[0].b_kmajor, st);
-  return launch_group_cfg<128, 128, 2, 2>(ks, n, gs[0].a_kmajor, gs[0].b_kmajor, st);
+  if (rope) {
+    if (!gs[0].a_kmajor || !gs[0].b_kmajor) return fail(-1, "gemm group: the rotary epilogue needs k-major operands");
+    if (rope->head_dim != 32 && rope->head_dim != 64 && rope->head_dim != 128) return fail(-1, "gemm group: head_dim %d", rope->head_dim);
+    for (int i = 0; i < n; ++i)
+      if (gs[i].r || gs[i].accumulate || gs[i].N % rope->head_dim || gs[i].ldc % 8)
+        return fail(-1, "gemm group: rotary epilogue on a product with residual, accumulation or partial heads");
+  }
+  if (tiles256 >= 192) return launch_group_cfg<256, 256, 2, 4>(ks, n, gs[0].a_kmajor, gs[0].b_kmajor, rope, st);
+  return launch_group_cfg<128, 128, 2, 2>(ks, n, gs[0].a_kmajor, gs[0].b_kmajor, rope, st);
 }
 
 }  // namespace dl

@@ -20,6 +20,9 @@ int launch_rope(void* z, int64_t batch, int64_t seq, int64_t n_heads, int64_t he
 // q and k of a layer in one launch (same positions and angles)
 int launch_rope_pair(void* q, void* k, int64_t batch, int64_t seq, int64_t n_q_heads, int64_t n_kv_heads,
                      int64_t head_dim, float base, int layout, int inverse, hipStream_t st);
+// cos and sin of angle(p, i) = p * base^(-2 i / head_dim) for p < seq, i < head_dim / 2, evaluated in
+// fp64 and stored as fp32 [seq][head_dim / 2]
+int launch_rope_table(float* cos, float* sin, int64_t seq, int64_t head_dim, float base, hipStream_t st);
 int launch_swiglu_fwd(const void* g, const void* u, int64_t n, void* a, hipStream_t st);
 int launch_swiglu_bwd(const void* g, const void* u, const void* da, int64_t n, void* dg, void* du,
                       hipStream_t st);
@@ -64,6 +67,11 @@ int launch_gemm(const GemmArgs& g, hipStream_t st);
 // Up to 8 independent problems with the same a_kmajor/b_kmajor in one launch (built for both operands
 // mn-major, the weight-gradient products, and both k-major, the forward projections).
 int launch_gemm_group(const GemmArgs* gs, int n, hipStream_t st);
+// The same for k-major products whose outputs are [tokens][heads][head_dim], with the rotary embedding
+// applied in the epilogue (on the fp32 accumulators) to the problems whose bit is set in rotate_mask.
+// cos, sin: [seq][head_dim / 2] fp32 (launch_rope_table); position of a row = row % seq.
+struct RopeEpilogue { const float *cos, *sin; int seq, head_dim, layout; unsigned rotate_mask; };
+int launch_gemm_group_rope(const GemmArgs* gs, int n, const RopeEpilogue* rope, hipStream_t st);
 // g = x Wg^T, u = x Wu^T and a = silu(g) * u (from the rounded g, u) in one launch.  x [T, K] with
 // leading dimension ldx, wg and wu [F, K] with ldw, g and u with ldgu, a with lda.  Only shapes
 // gemm_swiglu_applies() accepts (enough 256 x 256 tiles to fill the chip).
@@ -84,6 +92,14 @@ size_t attention_bwd_workspace(int64_t B, int64_t S, int64_t Hq, int64_t Hkv, in
 int launch_attention_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                          const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t dh,
                          void* dq, void* dk, void* dv, void* workspace, hipStream_t st);
+
+// The same for q and k that were rotated (rotary embedding) after their projections: dq and dk are
+// the gradients of the UNROTATED q and k, the inverse rotation being applied to the fp32 sums before
+// they are rounded.  rope_cos, rope_sin: [S][dh / 2] fp32 (launch_rope_table), or null for no rotation.
+int launch_attention_bwd_rope(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                              const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t dh,
+                              void* dq, void* dk, void* dv, void* workspace, const float* rope_cos,
+                              const float* rope_sin, int rope_layout, hipStream_t st);
 
 // ---- ce.hip
 size_t ce_workspace(int64_t T, int64_t V);

@@ -28,6 +28,42 @@ def _ws(nbytes):
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
 
 
+# ------------------------------------------------------------------ q, k, v projections with rotary epilogue
+@pytest.mark.parametrize("B,S,D,Hq,Hkv,dh,base,layout", [
+    (1, 128, 128, 4, 4, 32, 1e4, 0),        # 128 x 128 tiles, half a strip per head
+    (1, 128, 128, 4, 2, 32, 1e4, 1),
+    (2, 256, 192, 6, 2, 64, 1e4, 0),        # one strip per head
+    (2, 256, 192, 6, 2, 64, 1e4, 1),
+    (1, 384, 256, 3, 1, 128, 5e5, 0),       # partner-order tiles, 128 x 128
+    (1, 384, 256, 3, 1, 128, 5e5, 1),
+    (4, 2048, 128, 16, 8, 128, 5e5, 0),     # 256 x 256 tiles, partner order, several tiles per workgroup
+    (3, 2816, 64, 20, 4, 64, 1e4, 0),       # 256 x 256 tiles, ragged in T (8448 rows) and N (1280, 256)
+    (3, 2816, 64, 40, 8, 32, 1e4, 0),
+    (2, 8192, 64, 8, 2, 128, 5e5, 1),       # positions up to 8191, large base
+])
+def test_qkv_rope_forward(K, B, S, D, Hq, Hkv, dh, base, layout):
+    """q, k, v = h Wq^T, h Wk^T, h Wv^T in one launch with q and k rotated in the epilogue, against the
+    oracle's products and rotation."""
+    rng = np.random.default_rng(S + D + dh + layout)
+    T, QD, KD = B * S, Hq * dh, Hkv * dh
+    hb = _rand_bits(rng, (T, D))
+    wqb, wkb, wvb = _rand_bits(rng, (QD, D), 0.1), _rand_bits(rng, (KD, D), 0.1), _rand_bits(rng, (KD, D), 0.1)
+    h, wq, wk, wv = map(si.bf16_bits_to_f64, (hb, wqb, wkb, wvb))
+    phi = odl.rope_angles(S, dh, base)
+    q_ref = odl.rope_rotate((h @ wq.T).reshape(B, S, Hq, dh), phi, layout=layout)
+    k_ref = odl.rope_rotate((h @ wk.T).reshape(B, S, Hkv, dh), phi, layout=layout)
+    v_ref = (h @ wv.T).reshape(B, S, Hkv, dh)
+    hd, wqd, wkd, wvd = map(dev_bf16, (hb, wqb, wkb, wvb))
+    q = torch.full((T, QD), float("nan"), dtype=torch.bfloat16, device="cuda")
+    k = torch.full((T, KD), float("nan"), dtype=torch.bfloat16, device="cuda")
+    v = torch.full((T, KD), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = torch.full((K.qkv_rope_workspace_bytes(S, dh),), 0xFF, dtype=torch.uint8, device="cuda")
+    K.qkv_rope_forward(hd, wqd, wkd, wvd, B, S, D, Hq, Hkv, dh, base, layout, q, k, v, ws)
+    assert_close(q, q_ref, "q", rel_tol=8e-3)
+    assert_close(k, k_ref, "k", rel_tol=8e-3)
+    assert_close(v, v_ref, "v", rel_tol=8e-3)
+
+
 # ------------------------------------------------------------------ RMSNorm
 # rows wider than 4096 take the backward in column chunks (4096 + 1024, 2 x 4096, 4 x 4096)
 @pytest.mark.parametrize("T,D", [(300, 128), (1024, 768), (77, 2048), (130, 4096), (200, 5120), (1100, 8192), (70, 16384)])
@@ -170,8 +206,9 @@ def test_linear_wgrad_group(K):
     (2304, 128, 8200),      # fused, more tiles than CUs (a workgroup walks several), ragged F
 ])
 def test_linear_swiglu_forward(K, T, Kd, F):
-    """The gated pair g = x Wg^T, u = x Wu^T, a = silu(g) u in one call: against the oracle, and bit
-    for bit against the two products and the activation launched separately."""
+    """The gated pair g = x Wg^T, u = x Wu^T, a = silu(g) u in one call, against the oracle.  The fused
+    kernel takes the activation from the fp32 sums (one rounding, of a), the small-shape route from the
+    stored g and u; g and u themselves must equal the plain products bit for bit on either route."""
     rng = np.random.default_rng(T + F)
     xb, gb, ub = _rand_bits(rng, (T, Kd)), _rand_bits(rng, (F, Kd), 0.1), _rand_bits(rng, (F, Kd), 0.1)
     x, wg, wu = map(si.bf16_bits_to_f64, (xb, gb, ub))
@@ -181,12 +218,12 @@ def test_linear_swiglu_forward(K, T, Kd, F):
     g_ref, u_ref = x @ wg.T, x @ wu.T
     assert_close(g, g_ref, "g", rel_tol=8e-3)
     assert_close(u, u_ref, "u", rel_tol=8e-3)
-    assert_close(a, odl.swiglu_fwd(g_ref, u_ref), "a", rel_tol=1.2e-2)
-    g2, u2, a2 = (torch.full((T, F), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    fused = (T + 255) // 256 * ((2 * F + 255) // 256) >= 192
+    assert_close(a, odl.swiglu_fwd(g_ref, u_ref), "a", rel_tol=6e-3 if fused else 1.2e-2)
+    g2, u2 = (torch.full((T, F), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(2))
     K.linear_forward(xd, wgd, None, T, Kd, F, g2)
     K.linear_forward(xd, wud, None, T, Kd, F, u2)
-    K.swiglu_forward(g2, u2, T * F, a2)
-    for name, p, q in (("g", g, g2), ("u", u, u2), ("a", a, a2)):
+    for name, p, q in (("g", g, g2), ("u", u, u2)):
         assert torch.equal(p.view(torch.int16), q.view(torch.int16)), f"{name}: fused and separate launches differ"
 
 
@@ -197,8 +234,8 @@ def test_linear_swiglu_forward(K, T, Kd, F):
     (2304, 128, 8256),      # fused, more tiles than CUs, ragged F
 ])
 def test_linear_swiglu_backward(K, T, D, F):
-    """da = dy W_down and the SwiGLU gradient in one call: against the oracle, and bit for bit against
-    the input-gradient product and the activation gradient launched separately."""
+    """da = dy W_down and the SwiGLU gradient in one call, against the oracle (the fused kernel applies
+    the gradient to the fp32 sums of da, the small-shape route to da rounded to bf16)."""
     rng = np.random.default_rng(T + F + 3)
     dyb, wb = _rand_bits(rng, (T, D)), _rand_bits(rng, (D, F), 0.1)
     gb, ub = _rand_bits(rng, (T, F)), _rand_bits(rng, (T, F))
@@ -207,15 +244,9 @@ def test_linear_swiglu_backward(K, T, D, F):
     dg, du = (torch.full((T, F), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(2))
     K.linear_swiglu_backward(dyd, wd, gd, ud, T, D, F, dg, du, _ws(K.linear_swiglu_backward_workspace_bytes(T, D, F)))
     dg_ref, du_ref = odl.swiglu_bwd(g, u, dy @ w)
-    assert_close(dg, dg_ref, "dg", rel_tol=1.5e-2)
-    assert_close(du, du_ref, "du", rel_tol=1.5e-2)
-    da = torch.full((T, F), float("nan"), dtype=torch.bfloat16, device="cuda")
-    x_unused = torch.zeros((T, F), dtype=torch.bfloat16, device="cuda")
-    K.linear_backward(x_unused, wd, dyd, T, F, D, da, None, 0, _ws(K.linear_backward_workspace_bytes(T, F, D)))
-    dg2, du2 = torch.empty_like(dg), torch.empty_like(du)
-    K.swiglu_backward(gd, ud, da, T * F, dg2, du2)
-    for name, p, q in (("dg", dg, dg2), ("du", du, du2)):
-        assert torch.equal(p.view(torch.int16), q.view(torch.int16)), f"{name}: fused and separate launches differ"
+    fused = (T + 255) // 256 * ((F + 255) // 256) >= 192
+    assert_close(dg, dg_ref, "dg", rel_tol=8e-3 if fused else 1.5e-2)
+    assert_close(du, du_ref, "du", rel_tol=8e-3 if fused else 1.5e-2)
 
 
 @pytest.mark.parametrize("Kd,N,res", [(4096, 14336, False), (14336, 4096, True)])

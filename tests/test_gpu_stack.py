@@ -97,14 +97,13 @@ def test_stack_matches_oracle(K, head_chunk_rows):
 
 
 def test_stack_at_full_width_prefix_parity(K):
-    """The stack workload at its real widths and length (B1 S8192, 8B-shaped layers, V = 128256), two
-    layers deep - the launches are those of the four-layer workload, the oracle's share is what
-    limits the depth.  Causality makes the first P positions a closed sub-problem: logits[:P] depend
+    """The stack workload at its real widths, length and depth (B1 S8192, four 8B-shaped layers,
+    V = 128256).  Causality makes the first P positions a closed sub-problem: logits[:P] depend
     only on ids[:P], and with the upstream gradient of all later rows zeroed, dX0[:P], dE, dW_lm, the
     final gain's and every layer's weight gradients equal those of the P-token problem."""
     import math
     cfg = si.CONFIGS["8b_stack_layer"]
-    V, L, P = si.VOCAB_8B, 2, 128
+    V, L, P = si.VOCAB_8B, 4, 256
     assert cfg.batch == 1 and cfg.seq == 8192
     raw = si.make_stack_inputs(cfg, L, V, seed=1)
     T = cfg.tokens
@@ -120,9 +119,10 @@ def test_stack_at_full_width_prefix_parity(K):
     st = olm.stack_forward(*args)
     ref = olm.stack_backward(*args, st)
     hf = st["h_f"].reshape(P, cfg.d_model)
-    # two 8B-width layers of bf16 rounding noise under a K = 4096 dot product: the logits' error has a
-    # relative norm of 1.3 % (cosine 0.99992), whose maximum over 16 M elements is a 5.5-sigma tail
-    assert_close(got["logits_prefix"], hf @ s["w_lm"].T, "stack5:logits[prefix]", rel_tol=1e-1, cos_tol=0.9998)
+    # four 8B-width layers of bf16 rounding noise under a K = 4096 dot product: the logits' error has a
+    # relative norm of a percent or two, whose maximum over 33 M elements is a 5.5-sigma tail
+    r_lg, c_lg = assert_close(got["logits_prefix"], hf @ s["w_lm"].T, "stack5:logits[prefix]", rel_tol=1.5e-1, cos_tol=0.9995)
+    print(f"stack5 logits rel_err {r_lg:.3e} cos {c_lg:.6f}")
     assert_close(got["dx0"][:P], ref["dx0"].reshape(P, -1), "stack5:dx0[prefix]", rel_tol=np.inf)
     assert float(got["dx0"][P:].float().abs().max()) == 0.0
     for name in ("embed", "w_lm", "g_final"):
