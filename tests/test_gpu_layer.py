@@ -77,9 +77,9 @@ def test_layer_matches_oracle(K, name, override):
     g.forward()
     g.backward()
     torch.cuda.synchronize()
-    # the element-wise bound on y grows with the width (see Y_TOL_8B below: rounding of the MFMA operands
-    # to bf16 alone gives 2.2e-2 at d_model 4096); at 8192 it is taken half as wide again
-    rep = _check_layer(g, f, r, name, y_tol=1.5 * Y_TOL_8B if cfg.d_model > 4096 else REL_TOL)
+    # the element-wise bound on y grows with the width (see Y_TOL_8B below); for the one case wider than
+    # 4096 the bf16-operand floor on these very inputs is 3.4e-2 and the GPU measures 3.5e-2
+    rep = _check_layer(g, f, r, name, y_tol=Y_TOL_D8192 if cfg.d_model > 4096 else REL_TOL)
     print(name, override, {k: (f"{a:.2e}", f"{b:.6f}") for k, (a, b) in rep.items()})
 
 
@@ -170,13 +170,20 @@ def test_layer_replays_from_a_hip_graph(K, name):
             assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"{name}: {n} differs between replay and eager"
 
 
-# At D = 4096, F = 14336 the element-wise metric (max over ~1e6 outputs of |err| / max(|ref|, rms))
-# of ANY pipeline that rounds MFMA operands to bf16 exceeds 2e-2: rounding only h1, q, k, v, o, h2, a
-# and y (each needed as an MFMA operand or as the output) in an otherwise exact fp64 evaluation gives
-# 2.2e-2 (tests/test_oracle_pins.py::test_bf16_operand_rounding_floor_at_8b_width).  The bound used at
-# this width is therefore 3e-2 on that metric, together with the two companion figures: the
-# infinity-norm ratio and the fraction of elements above 2e-2.
-Y_TOL_8B = 3e-2
+# At D = 4096, F = 14336 the element-wise metric (max over the outputs of |err| / max(|ref|, rms)) of
+# ANY pipeline that rounds MFMA operands to bf16 exceeds 2e-2: rounding only h1, q, k, v, o, h2, a and
+# y (each needed as an MFMA operand or as the output) in an otherwise exact fp64 evaluation gives
+# 2.43e-2 on the very inputs of test_8b_shape_prefix_parity (2 x 2048 positions, 16.8 M outputs;
+# 2.48e-2 with y1 rounded as well), and 2.2e-2 on 64 positions
+# (tests/test_oracle_pins.py::test_bf16_operand_rounding_floor_at_8b_width).  The GPU measures 2.63e-2
+# there: the floor plus the rounding of the softmax weights to bf16 and fp32 summation.  The bound at
+# this width is the measured value with a 5 % margin, together with two companion figures: the
+# infinity-norm ratio (bound 1e-2, measured 5e-3) and the fraction of elements above 2e-2 (bound 1e-3,
+# measured 7e-6).  The stated bar of 2e-2 on this metric is NOT met at this width and cannot be with
+# bf16 operands.
+Y_TOL_8B = 2.75e-2
+# d_model 8192 (one case of test_layer_matches_oracle): same emulation on its inputs 3.4e-2, GPU 3.5e-2
+Y_TOL_D8192 = 3.8e-2
 
 
 def _assert_y_8b(got, ref, name):

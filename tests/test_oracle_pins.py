@@ -471,17 +471,23 @@ def test_inputs_are_seeded_and_distributed_as_stated():
 
 
 # ------------------------------------------------------------------ what bf16 MFMA operands cost
-def test_bf16_operand_rounding_floor_at_8b_width():
-    """Evidence for the element-wise bound used at the 8B width: evaluate the layer exactly (fp64)
-    but round to bf16 the tensors that must be bf16 because they feed an MFMA or are the output
+@pytest.mark.parametrize("name,override,lo,hi", [
+    ("8b", {"batch": 1, "seq": 64}, 1.7e-2, 3e-2),
+    # the wider-than-4096 case of the GPU layer tests, on its own inputs
+    ("tiny", {"seq": 256, "d_model": 8192, "n_q_heads": 8, "n_kv_heads": 2, "head_dim": 128, "d_ff": 1024}, 2.8e-2, 3.8e-2),
+])
+def test_bf16_operand_rounding_floor_at_8b_width(name, override, lo, hi):
+    """Evidence for the element-wise bound used at widths of 4096 and more: evaluate the layer exactly
+    (fp64) but round to bf16 the tensors that must be bf16 because they feed an MFMA or are the output
     (h1, rotated q and k, v, o, h2, a, y - nothing else).  At D = 4096, F = 14336 the metric
-    max |err| / max(|ref|, rms(ref)) over y already exceeds 2e-2, while the infinity-norm ratio and
-    the cosine stay far inside their bars.  64 positions keep this within a CPU test's budget."""
-    cfg8 = si.CONFIGS["8b"]
-    P = 64
-    cfg = cfg8.with_(batch=1, seq=P)
+    max |err| / max(|ref|, rms(ref)) over y already exceeds 2e-2 (2.43e-2 on the 2 x 2048 positions
+    of the GPU test, which a CPU test cannot afford; 2.2e-2 on the 64 positions here), while the
+    infinity-norm ratio and the cosine stay far inside their bars."""
+    cfg = si.CONFIGS[name].with_(**override)
     rng = np.random.Generator(np.random.PCG64(0))
-    x = si.bf16_bits_to_f64(si._normal_bf16(rng, (1, P, cfg.d_model)))
+    x = si.bf16_bits_to_f64(si._normal_bf16(rng, (cfg.batch, cfg.seq, cfg.d_model)))
+    if name != "8b":
+        si._normal_bf16(rng, (cfg.batch, cfg.seq, cfg.d_model))     # dy: keeps the draw order of make_layer_inputs
     w = si.to_f64(si.draw_layer_weights(rng, cfg))
     rnd = lambda a: si.bf16_bits_to_f64(si.f32_to_bf16_bits(a.astype(np.float32)))
     f = dl.layer_forward(cfg, x, w)
@@ -502,5 +508,5 @@ def test_bf16_operand_rounding_floor_at_8b_width():
     metric = np.max(np.abs(y - ref) / np.maximum(np.abs(ref), rms))
     inf_ratio = np.abs(y - ref).max() / np.abs(ref).max()
     cos = np.sum(y * ref) / np.linalg.norm(y) / np.linalg.norm(ref)
-    assert 1.7e-2 < metric < 3e-2, metric
-    assert inf_ratio < 1e-2 and cos > 0.99998
+    assert lo < metric < hi, metric
+    assert inf_ratio < 1e-2 and cos > 0.99997
