@@ -132,12 +132,53 @@ def bench_stack(args, torch, K, si, dev_bf16):
         "loss": float(loss.item())}))
 
 
+def bench_optimizer(args, torch, K, si):
+    """The optimizer step of one 8B-shaped layer (not the headline line): global-norm clipping and AdamW
+    over the layer's nine parameter tensors (218 M bf16 parameters, fp32 moments).  Both kernels are
+    bound by HBM: 2 bytes per element for the norm, 22 for the update."""
+    cfg = si.CONFIGS["8b"]
+    shapes = si.weight_shapes(cfg)
+    P = [torch.empty(shapes[n], dtype=torch.bfloat16, device="cuda").normal_(0, 0.02) for n in si.WEIGHT_NAMES]
+    G = [torch.empty_like(p).normal_(0, 1e-3) for p in P]
+    M = [torch.zeros(p.shape, dtype=torch.float32, device="cuda") for p in P]
+    V = [torch.zeros(p.shape, dtype=torch.float32, device="cuda") for p in P]
+    sq = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(K.grad_sq_norm_workspace_bytes(G), 256), dtype=torch.uint8, device="cuda")
+    n = sum(p.numel() for p in P)
+    state = {"t": 0}
+
+    def step():
+        state["t"] += 1
+        K.grad_sq_norm(G, sq, 0, ws)
+        K.adamw_step(P, G, M, V, state["t"], 3e-4, 0.9, 0.95, 1e-8, 0.1, 1.0, sq)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    nbytes = 24.0 * n
+    print(json.dumps({
+        "metric": "optimizer step (global-norm clip + AdamW) GB/s of algorithmic HBM bytes", "value": nbytes / (ms * 1e-3) / 1e9,
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"clip + AdamW over the 9 parameter tensors of one 8B-shaped layer ({n} parameters)", "name": "optimizer",
+                   "bytes_per_step": nbytes},
+        "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                     "frac": nbytes / (ms * 1e-3) / 1e9 / 8000.0, "traffic": None}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b", "70b_width", "stack"])
+    ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b", "70b_width", "stack", "optimizer"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=4096)
     ap.add_argument("--copy-probe", action="store_true",
@@ -158,6 +199,8 @@ def main():
     torch.cuda.set_device(0)
     if args.config == "stack":
         return bench_stack(args, torch, K, si, dev_bf16)
+    if args.config == "optimizer":
+        return bench_optimizer(args, torch, K, si)
     cfg = si.CONFIGS[args.config]
     inp = si.make_layer_inputs(cfg, seed=0)
     x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])

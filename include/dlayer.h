@@ -259,6 +259,34 @@ int embed_forward(const void* table, const int64_t* ids, int64_t T, int64_t V, i
 int embed_backward(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D,
                    void* dtable, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Optimizer step.  The paper's Training Pipeline paragraph speaks of training steps and names no
+ * optimizer; the reading taken is the usual one for this model family: clipping of the gradients by
+ * their global norm, then AdamW (Adam with decoupled weight decay).  Parameters and gradients are
+ * bf16, the two moment tensors fp32, the arithmetic fp32.  Up to 16 tensors per call; all lists are
+ * host arrays of length n holding device pointers / element counts (each a multiple of 8).
+ * ------------------------------------------------------------------------------------------ */
+
+/* *sq_norm (device f32) = sum over every element of the n gradient tensors of g^2, or that sum added
+ * to the value already there when accumulate != 0 (a model with more than 16 tensors takes several
+ * calls).  Summed in a fixed order: the result is bitwise reproducible.
+ * workspace (device): grad_sq_norm_workspace_bytes(n, numel).                                      */
+size_t grad_sq_norm_workspace_bytes(int32_t n, const int64_t* numel);
+int grad_sq_norm(int32_t n, const void* const* grads, const int64_t* numel, float* sq_norm,
+                 int accumulate, void* workspace, void* stream);
+
+/* One AdamW update of n tensors, in place (step counts from 1):
+ *   g' = g * min(1, max_grad_norm / (sqrt(*sq_norm) + 1e-6))      (g' = g when sq_norm is NULL)
+ *   p <- p (1 - lr weight_decay);  m <- beta1 m + (1 - beta1) g';  v <- beta2 v + (1 - beta2) g'^2
+ *   p <- p - lr / (1 - beta1^step) * m / (sqrt(v) / sqrt(1 - beta2^step) + eps)
+ * sq_norm is read on the device (the value grad_sq_norm left there): no host synchronisation between
+ * the two calls.  params bf16 (updated), grads bf16 (read only), exp_avg = m and exp_avg_sq = v fp32
+ * (updated).                                                                                      */
+int adamw_step(int32_t n, void* const* params, const void* const* grads, float* const* exp_avg,
+               float* const* exp_avg_sq, const int64_t* numel, int64_t step, float lr, float beta1,
+               float beta2, float eps, float weight_decay, float max_grad_norm, const float* sq_norm,
+               void* stream);
+
 #ifdef __cplusplus
 }
 #endif

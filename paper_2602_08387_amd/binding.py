@@ -18,6 +18,7 @@ EXPORTED_SYMBOLS = (
     "linear_swiglu_backward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
     "attention_forward", "attention_backward_workspace_bytes", "attention_backward",
     "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",
+    "grad_sq_norm_workspace_bytes", "grad_sq_norm", "adamw_step",
 )
 
 
@@ -85,6 +86,9 @@ def _load():
         "swiglu_backward": (C.c_int, [vp, vp, vp, i64, vp, vp, vp]),
         "embed_forward": (C.c_int, [vp, vp, i64, i64, i64, vp, vp]),
         "embed_backward": (C.c_int, [vp, vp, i64, i64, i64, vp, vp]),
+        "grad_sq_norm_workspace_bytes": (sz, [i32, vp]),
+        "grad_sq_norm": (C.c_int, [i32, vp, vp, vp, C.c_int, vp, vp]),
+        "adamw_step": (C.c_int, [i32, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, f32, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(l, name)
@@ -266,3 +270,29 @@ def embed_forward(table, ids, T, V, D, x0, stream=None):
 
 def embed_backward(dx0, ids, T, V, D, dtable, stream=None):
     _check(lib.embed_backward(_p(dx0), _p(ids), T, V, D, _p(dtable), _stream(stream)), "embed_backward")
+
+
+def _ptr_list(ts):
+    return (C.c_void_p * len(ts))(*[_p(t) for t in ts])
+
+
+def _numel_list(ts):
+    return (C.c_int64 * len(ts))(*[int(t.numel()) for t in ts])
+
+
+def grad_sq_norm_workspace_bytes(grads) -> int:
+    return lib.grad_sq_norm_workspace_bytes(len(grads), _numel_list(grads))
+
+
+def grad_sq_norm(grads, sq_norm, accumulate, workspace, stream=None):
+    _check(lib.grad_sq_norm(len(grads), _ptr_list(grads), _numel_list(grads), _p(sq_norm), int(accumulate),
+                            _p(workspace), _stream(stream)), "grad_sq_norm")
+
+
+def adamw_step(params, grads, exp_avg, exp_avg_sq, step, lr, beta1, beta2, eps, weight_decay, max_grad_norm,
+               sq_norm, stream=None):
+    n = len(params)
+    assert len(grads) == len(exp_avg) == len(exp_avg_sq) == n
+    _check(lib.adamw_step(n, _ptr_list(params), _ptr_list(grads), _ptr_list(exp_avg), _ptr_list(exp_avg_sq),
+                          _numel_list(params), int(step), lr, beta1, beta2, eps, weight_decay, max_grad_norm,
+                          _p(sq_norm), _stream(stream)), "adamw_step")

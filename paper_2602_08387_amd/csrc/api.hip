@@ -569,6 +569,53 @@ int attention_backward(const void* q, const void* k, const void* v, const void* 
                               workspace, (hipStream_t)stream);
 }
 
+static int opt_args_ok(const char* who, int32_t n, const int64_t* numel) {
+  REQUIRE(n >= 1 && n <= kOptMaxTensors, "%s: 1..%d tensors per call, got %d", who, kOptMaxTensors, (int)n);
+  REQUIRE(numel != nullptr, "%s: numel is null", who);
+  int64_t chunks = 0;
+  for (int i = 0; i < n; ++i) {
+    REQUIRE(numel[i] > 0 && numel[i] % 8 == 0, "%s: numel[%d] must be a positive multiple of 8", who, i);
+    chunks += (numel[i] + 16383) / 16384;
+  }
+  REQUIRE(chunks < ((int64_t)1 << 31), "%s: too many elements for one call", who);
+  return 0;
+}
+
+size_t grad_sq_norm_workspace_bytes(int32_t n, const int64_t* numel) {
+  if (n < 1 || n > kOptMaxTensors || !numel) return 0;
+  for (int i = 0; i < n; ++i) if (numel[i] <= 0) return 0;
+  return up256((size_t)opt_chunks(n, numel) * sizeof(float));
+}
+
+int grad_sq_norm(int32_t n, const void* const* grads, const int64_t* numel, float* sq_norm, int accumulate,
+                 void* workspace, void* stream) {
+  TRY(opt_args_ok("grad_sq_norm", n, numel));
+  REQUIRE(grads != nullptr && sq_norm != nullptr, "grad_sq_norm: grads or sq_norm is null");
+  REQUIRE_PTR(workspace);
+  for (int i = 0; i < n; ++i)
+    REQUIRE(grads[i] != nullptr && aligned16(grads[i]), "grad_sq_norm: grads[%d] is null or not 16-byte aligned", i);
+  TRY(check_device());
+  return launch_grad_sq_norm(n, grads, numel, sq_norm, (float*)workspace, accumulate ? 1 : 0, (hipStream_t)stream);
+}
+
+int adamw_step(int32_t n, void* const* params, const void* const* grads, float* const* exp_avg, float* const* exp_avg_sq,
+               const int64_t* numel, int64_t step, float lr, float beta1, float beta2, float eps, float weight_decay,
+               float max_grad_norm, const float* sq_norm, void* stream) {
+  TRY(opt_args_ok("adamw_step", n, numel));
+  REQUIRE(params && grads && exp_avg && exp_avg_sq, "adamw_step: null tensor list");
+  REQUIRE(step >= 1, "adamw_step: the step counter starts at 1");
+  REQUIRE(lr >= 0.f && beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f && eps >= 0.f && weight_decay >= 0.f,
+          "adamw_step: need lr >= 0, 0 <= beta < 1, eps >= 0, weight_decay >= 0");
+  REQUIRE(sq_norm == nullptr || max_grad_norm > 0.f, "adamw_step: max_grad_norm must be positive when sq_norm is given");
+  for (int i = 0; i < n; ++i)
+    REQUIRE(params[i] && grads[i] && exp_avg[i] && exp_avg_sq[i] && aligned16(params[i]) && aligned16(grads[i]) &&
+                aligned16(exp_avg[i]) && aligned16(exp_avg_sq[i]),
+            "adamw_step: a pointer of tensor %d is null or not 16-byte aligned", i);
+  TRY(check_device());
+  return launch_adamw(n, params, grads, exp_avg, exp_avg_sq, numel, step, lr, beta1, beta2, eps, weight_decay,
+                      max_grad_norm, sq_norm, (hipStream_t)stream);
+}
+
 int swiglu_forward(const void* g, const void* u, int64_t n, void* a, void* stream) {
   REQUIRE(n > 0 && n % 8 == 0, "swiglu_forward: n must be a positive multiple of 8");
   REQUIRE_PTR(g); REQUIRE_PTR(u); REQUIRE_PTR(a);

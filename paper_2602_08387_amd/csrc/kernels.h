@@ -114,4 +114,16 @@ int64_t ce_static_max_rows();
 int launch_ce_static(const void* logits, const int64_t* targets, int64_t T, int64_t V, float grad_scale,
                      float* loss, void* dlogits, hipStream_t st);
 
+// ---- optimizer.hip
+constexpr int kOptMaxTensors = 16;
+// number of 16384-element chunks the tensors of a call split into (= floats of workspace the norm needs)
+int64_t opt_chunks(int n, const int64_t* numel);
+// *sq_norm (+)= sum over all elements of all n gradient tensors of g^2 (fp32, fixed summation order)
+int launch_grad_sq_norm(int n, const void* const* g, const int64_t* numel, float* sq_norm, float* partial,
+                        int accumulate, hipStream_t st);
+// AdamW on n tensors; sq_norm (device, may be null): gradients are scaled by min(1, max_norm / (sqrt(*sq_norm) + 1e-6))
+int launch_adamw(int n, void* const* p, const void* const* g, float* const* m, float* const* v, const int64_t* numel,
+                 int64_t step, float lr, float beta1, float beta2, float eps, float weight_decay, float max_norm,
+                 const float* sq_norm, hipStream_t st);
+
 }  // namespace dl
