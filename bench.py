@@ -96,6 +96,7 @@ def bench_stack(args, torch, K, si, dev_bf16):
     dW = [{n: torch.empty_like(t) for n, t in W[l].items()} for l in range(L)]
     ws_head = u8(K.lm_head_ce_workspace_bytes(T, D, V, 0))
     ws_norm = u8(K.rmsnorm_backward_workspace_bytes(T, D))
+    ws_emb = u8(K.embed_backward_workspace_bytes(T, V))
 
     def step():
         K.embed_forward(E, ids, T, V, D, xs[0])
@@ -108,7 +109,7 @@ def bench_stack(args, torch, K, si, dev_bf16):
         for l in reversed(range(L)):
             K.dlayer_backward(cfg, xs[l], W[l], a, saved[l], b, dW[l], 0, ws)
             a, b = b, a
-        K.embed_backward(a, ids, T, V, D, dE)
+        K.embed_backward(a, ids, T, V, D, dE, ws_emb)
 
     for _ in range(args.warmup):
         step()

@@ -253,11 +253,15 @@ int swiglu_backward(const void* g, const void* u, const void* da, int64_t n, voi
 /* x0[t, :] = table[ids[t], :].  table [V, D] bf16, ids [T] int64 in [0, V), x0 [T, D] bf16.  */
 int embed_forward(const void* table, const int64_t* ids, int64_t T, int64_t V, int64_t D,
                   void* x0, void* stream);
-/* dtable[v, :] = sum over t with ids[t] == v of dx0[t, :] (rows of absent ids are zero).
- * Deterministic (no atomics): fp32 sum in token order, bf16 result.  dtable [V, D] bf16 is
- * overwritten.                                                                              */
+/* dtable[v, :] = sum over t with ids[t] == v of dx0[t, :] (rows of absent ids are zero; ids outside
+ * [0, V) are skipped).  Deterministic: the tokens of an id are listed, sorted and summed in fp32 in
+ * ascending token order (interleaved partial sums, combined in a fixed order), bf16 result; no
+ * floating-point atomics, bitwise reproducible.  An id with more than four tokens is summed by one
+ * workgroup per 128 columns, whatever its frequency.  dtable [V, D] bf16 is overwritten.
+ * workspace (device): embed_backward_workspace_bytes(T, V), about (3 V + 2.2 T) ints.         */
+size_t embed_backward_workspace_bytes(int64_t T, int64_t V);
 int embed_backward(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D,
-                   void* dtable, void* stream);
+                   void* dtable, void* workspace, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Optimizer step.  The paper's Training Pipeline paragraph speaks of training steps and names no

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = (
     "linear_forward", "qkv_rope_workspace_bytes", "qkv_rope_forward", "linear_swiglu_forward", "linear_swiglu_backward_workspace_bytes",
     "linear_swiglu_backward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
     "attention_forward", "attention_backward_workspace_bytes", "attention_backward",
-    "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward",
+    "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward_workspace_bytes", "embed_backward",
     "grad_sq_norm_workspace_bytes", "grad_sq_norm", "adamw_step",
 )
 
@@ -85,7 +85,8 @@ def _load():
         "swiglu_forward": (C.c_int, [vp, vp, i64, vp, vp]),
         "swiglu_backward": (C.c_int, [vp, vp, vp, i64, vp, vp, vp]),
         "embed_forward": (C.c_int, [vp, vp, i64, i64, i64, vp, vp]),
-        "embed_backward": (C.c_int, [vp, vp, i64, i64, i64, vp, vp]),
+        "embed_backward_workspace_bytes": (sz, [i64, i64]),
+        "embed_backward": (C.c_int, [vp, vp, i64, i64, i64, vp, vp, vp]),
         "grad_sq_norm_workspace_bytes": (sz, [i32, vp]),
         "grad_sq_norm": (C.c_int, [i32, vp, vp, vp, C.c_int, vp, vp]),
         "adamw_step": (C.c_int, [i32, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, f32, vp, vp]),
@@ -268,8 +269,12 @@ def embed_forward(table, ids, T, V, D, x0, stream=None):
     _check(lib.embed_forward(_p(table), _p(ids), T, V, D, _p(x0), _stream(stream)), "embed_forward")
 
 
-def embed_backward(dx0, ids, T, V, D, dtable, stream=None):
-    _check(lib.embed_backward(_p(dx0), _p(ids), T, V, D, _p(dtable), _stream(stream)), "embed_backward")
+def embed_backward_workspace_bytes(T, V) -> int:
+    return lib.embed_backward_workspace_bytes(T, V)
+
+
+def embed_backward(dx0, ids, T, V, D, dtable, workspace, stream=None):
+    _check(lib.embed_backward(_p(dx0), _p(ids), T, V, D, _p(dtable), _p(workspace), _stream(stream)), "embed_backward")
 
 
 def _ptr_list(ts):

@@ -638,13 +638,16 @@ int embed_forward(const void* table, const int64_t* ids, int64_t T, int64_t V, i
   return launch_embed_fwd(table, ids, T, V, D, x0, (hipStream_t)stream);
 }
 
+size_t embed_backward_workspace_bytes(int64_t T, int64_t V) { return T > 0 && V > 0 ? embed_bwd_workspace(T, V) : 0; }
+
 int embed_backward(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D, void* dtable,
-                   void* stream) {
-  REQUIRE(T > 0 && V > 0 && D > 0 && D % 8 == 0 && T < ((int64_t)1 << 31), "embed_backward: need T, V > 0 and D %% 8 == 0");
-  REQUIRE_PTR(dx0); REQUIRE_PTR(dtable);
+                   void* workspace, void* stream) {
+  REQUIRE(T > 0 && V > 0 && D > 0 && D % 8 == 0 && T < ((int64_t)1 << 30) && V < ((int64_t)1 << 30),
+          "embed_backward: need 0 < T, V < 2^30 and D %% 8 == 0");
+  REQUIRE_PTR(dx0); REQUIRE_PTR(dtable); REQUIRE_PTR(workspace);
   REQUIRE(ids != nullptr, "embed_backward: ids is null");
   TRY(check_device());
-  return launch_embed_bwd(dx0, ids, T, V, D, dtable, (hipStream_t)stream);
+  return launch_embed_bwd(dx0, ids, T, V, D, dtable, workspace, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -599,106 +599,275 @@ int launch_embed_fwd(const void* table, const int64_t* ids, int64_t T, int64_t V
   return check_launch("embed_forward");
 }
 
-__global__ __launch_bounds__(256) void zero_kernel(u32x4* p, int64_t nvec) {
-  const u32x4 z = {0, 0, 0, 0};
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec;
-       i += (int64_t)gridDim.x * blockDim.x)
-    p[i] = z;
+// ------------------------------------------------------------------------------------------
+// Embedding gradient dtable[v] = sum of the rows dx0[t] with ids[t] == v, deterministic and without
+// floating-point atomics.  The tokens of every id are gathered into a list (integer atomics: which slot
+// a token gets depends on scheduling, the SET of tokens in a list does not), the list is sorted, and
+// the rows are summed in ascending token order by a fixed assignment of rows to partial sums.  So the
+// result is bitwise reproducible.  Ids with up to four tokens (one workgroup each) and ids with more (a
+// sorting pass, then one workgroup per 128 columns) take different kernels; which one depends on the
+// count alone.
+//   count[v]   tokens with id v                       (embed_count_kernel)
+//   start[v]   first slot of id v's segment of list   (embed_segments_kernel)
+//   list[...]  token indices grouped by id, slot[t] = position of t in list    (embed_fill_kernel)
+//   owner of an id = the token that drew the first slot of its group: its workgroups sum the rows
+// ------------------------------------------------------------------------------------------
+constexpr int kEmbSortMax = 8192;   // tokens of one id that are sorted in LDS (ids beyond that are walked)
+constexpr int kEmbVecPerBlock = 16; // 16-byte column vectors per workgroup (128 columns) of the heavy kernel
+constexpr int kEmbLight = 4;        // ids with at most this many tokens: one workgroup sums the whole row, no LDS
+
+__global__ __launch_bounds__(256) void embed_zero_ints_kernel(int* p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0;
 }
 
-// One block per token t.  The block owns row ids[t] iff no earlier token has the same id; it then
-// sums (fp32, ascending token order: the result does not depend on scheduling) the gradient rows of
-// every token with that id.  The tokens are scanned in segments of kEmbSeg: all threads mark the
-// matches of a segment in an LDS bitmap (atomic OR, so the bitmap is the same however the threads are
-// scheduled), then every thread walks the set bits in order for its columns.
-constexpr int kEmbSeg = 8192;
-__global__ __launch_bounds__(256) void embed_bwd_kernel(const bf16_t* __restrict__ dx0,
-                                                        const int64_t* __restrict__ ids,
-                                                        bf16_t* __restrict__ dtable, int64_t T,
-                                                        int64_t V, int D) {
-  __shared__ int earlier;
-  __shared__ unsigned bits[kEmbSeg / 32];
-  const int64_t t = blockIdx.x;
+__global__ __launch_bounds__(256) void embed_count_kernel(const int64_t* __restrict__ ids, int T, int64_t V, int* count) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
   const int64_t id = ids[t];
-  if (id < 0 || id >= V) return;  // uniform over the block
-  if (threadIdx.x == 0) earlier = 0;
-  __syncthreads();
-  for (int64_t s = threadIdx.x; s < t; s += blockDim.x)
-    if (ids[s] == id) earlier = 1;
-  __syncthreads();
-  if (earlier) return;            // uniform over the block
-  const int nv = D >> 3;
-  constexpr int NC = 2;           // column vectors per thread and pass: D up to 4096 in one pass
-  bf16x8* out = reinterpret_cast<bf16x8*>(dtable + id * D);
-  for (int c0 = 0; c0 < nv; c0 += NC * 256) {
-    float a[NC][8];
+  if (id >= 0 && id < V) atomicAdd(&count[id], 1);
+}
+
+// start[v] = first slot of id v's segment of `list`.  The segments only have to be disjoint, not in id
+// order, so they are handed out from a running cursor: one atomic per wavefront (the lanes' counts are
+// prefix-summed with shuffles).  Where a segment lands depends on scheduling; what it holds does not.
+__global__ __launch_bounds__(256) void embed_segments_kernel(const int* __restrict__ count, int* __restrict__ start, int V,
+                                                             int* cursor) {
+  const int v = blockIdx.x * 256 + threadIdx.x, lane = threadIdx.x & 63;
+  const int c = v < V ? count[v] : 0;
+  int incl = c;
 #pragma unroll
-    for (int q = 0; q < NC; ++q)
+  for (int off = 1; off < 64; off <<= 1) {
+    const int x = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += x;
+  }
+  const int total = __shfl(incl, 63, 64);
+  int base = 0;
+  if (lane == 63 && total > 0) base = atomicAdd(cursor, total);
+  base = __shfl(base, 63, 64);
+  if (v < V) start[v] = base + incl - c;
+}
+
+__global__ __launch_bounds__(256) void embed_fill_kernel(const int64_t* __restrict__ ids, int T, int64_t V,
+                                                         const int* __restrict__ count, const int* __restrict__ start, int* fill,
+                                                         int* __restrict__ list, int* __restrict__ slot, int* heavy,
+                                                         int* n_heavy) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int64_t id = ids[t];
+  if (id < 0 || id >= V) { slot[t] = -1; return; }
+  const int first = start[id], s = first + atomicAdd(&fill[id], 1);
+  list[s] = t;
+  slot[t] = s;
+  // ids with more than kEmbLight tokens are summed by the heavy kernel; the order of this list does not
+  // matter (every entry is worked on independently)
+  if (s == first && count[id] > kEmbLight) heavy[atomicAdd(n_heavy, 1)] = (int)id;
+}
+
+// rows of dtable no token points at
+__global__ __launch_bounds__(256) void embed_zero_rows_kernel(const int* __restrict__ count, u32x4* __restrict__ dtable, int64_t V,
+                                                              int row_vec) {
+  const u32x4 z = {0, 0, 0, 0};
+  for (int64_t v = blockIdx.x; v < V; v += gridDim.x) {
+    if (count[v] != 0) continue;
+    u32x4* row = dtable + v * row_vec;
+    for (int c = threadIdx.x; c < row_vec; c += 256) row[c] = z;
+  }
+}
+
+// Ids with at most kEmbLight tokens (nearly all of them unless the ids are very skewed).  One workgroup
+// per token; the token that owns its id sorts the id's few tokens in registers and sums their rows with the
+// same rule as the heavy kernel: row of rank r to partial sum r % 4, then (s0 + s1) + (s2 + s3).
+__global__ __launch_bounds__(256) void embed_sum_light_kernel(const bf16_t* __restrict__ dx0, const int64_t* __restrict__ ids,
+                                                              const int* __restrict__ count, const int* __restrict__ start,
+                                                              const int* __restrict__ list, const int* __restrict__ slot,
+                                                              bf16_t* __restrict__ dtable, int T, int64_t V, int D) {
+  const int t = blockIdx.x;
+  const int64_t id = ids[t];
+  if (id < 0 || id >= V) return;
+  const int first = start[id], L = count[id];
+  if (slot[t] != first || L > kEmbLight) return;
+  int r[kEmbLight];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) a[q][e] = 0.f;
-    for (int64_t base = t - t % kEmbSeg; base < T; base += kEmbSeg) {
-      __syncthreads();
-      for (int w = threadIdx.x; w < kEmbSeg / 32; w += 256) bits[w] = 0u;
-      __syncthreads();
-      for (int k = threadIdx.x; k < kEmbSeg; k += 256) {
-        const int64_t s = base + k;
-        if (s >= t && s < T && ids[s] == id) atomicOr(&bits[k >> 5], 1u << (k & 31));
-      }
-      __syncthreads();
-      // one row ahead: the loads of the next matching row go out before the current one is summed
-      // (a frequent token has thousands of rows, all summed by this one workgroup)
-      bf16x8 cur[NC], nxt[NC];
-      bool have = false;
-      auto add_cur = [&]() {
+  for (int i = 0; i < kEmbLight; ++i) r[i] = i < L ? list[first + i] : T;
 #pragma unroll
-        for (int q = 0; q < NC; ++q) {
-          const int c = c0 + q * 256 + threadIdx.x;
-          if (c < nv) {
+  for (int i = 0; i < kEmbLight; ++i)       // sorting network for four keys (padding sorts last)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) a[q][e] += (float)cur[q][e];
-          }
-        }
-      };
-      for (int w = 0; w < kEmbSeg / 32; ++w) {
-        unsigned m = bits[w];
-        while (m) {
-          const int k = w * 32 + __builtin_ctz(m);
-          m &= m - 1;
-          const bf16x8* row = reinterpret_cast<const bf16x8*>(dx0 + (base + k) * D);
+    for (int j = 0; j + 1 < kEmbLight - i; ++j)
+      if (r[j] > r[j + 1]) { const int x = r[j]; r[j] = r[j + 1]; r[j + 1] = x; }
+  static_assert(kEmbLight == 4, "one row per partial sum");
+  for (int c = threadIdx.x; c < (D >> 3); c += 256) {
+    float a[4][8];
 #pragma unroll
-          for (int q = 0; q < NC; ++q) {
-            const int c = c0 + q * 256 + threadIdx.x;
-            if (c < nv) nxt[q] = row[c];
-          }
-          if (have) add_cur();
+    for (int i = 0; i < 4; ++i) {
+      bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (i < L) v = *reinterpret_cast<const bf16x8*>(dx0 + (int64_t)r[i] * D + c * 8);
 #pragma unroll
-          for (int q = 0; q < NC; ++q) cur[q] = nxt[q];
-          have = true;
-        }
-      }
-      if (have) add_cur();
+      for (int e = 0; e < 8; ++e) a[i][e] = (float)v[e];
     }
+    bf16x8 o;
 #pragma unroll
-    for (int q = 0; q < NC; ++q) {
-      const int c = c0 + q * 256 + threadIdx.x;
-      if (c < nv) {
-        bf16x8 o;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)a[q][e];
-        out[c] = o;
+    for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((a[0][e] + a[1][e]) + (a[2][e] + a[3][e]));
+    *reinterpret_cast<bf16x8*>(dtable + id * D + c * 8) = o;
+  }
+}
+
+// Sorts the token list of every id on the heavy list, in place: one workgroup per id at a time.  Lists
+// of up to kEmbSortMax tokens go through a bitonic network in LDS; a longer one is rebuilt in order by
+// walking all ids (a bitmap per piece of kEmbSortMax tokens, positions from prefix sums of its words).
+__global__ __launch_bounds__(1024) void embed_sort_kernel(const int64_t* __restrict__ ids, const int* __restrict__ count,
+                                                         const int* __restrict__ start, int* list,
+                                                         const int* __restrict__ heavy, const int* __restrict__ n_heavy, int T) {
+  __shared__ int lst[kEmbSortMax];
+  __shared__ unsigned bits[kEmbSortMax / 32];
+  __shared__ int wpre[kEmbSortMax / 32 + 1];
+  const int nh = *n_heavy;
+  for (int hi = blockIdx.x; hi < nh; hi += gridDim.x) {
+    const int64_t id = heavy[hi];
+    const int first = start[id], L = count[id];
+    __syncthreads();   // the previous id's list has been written back
+    if (L <= kEmbSortMax) {
+      int n2 = 1;
+      while (n2 < L) n2 <<= 1;
+      for (int i = threadIdx.x; i < n2; i += 1024) lst[i] = i < L ? list[first + i] : T;
+      __syncthreads();
+      for (int k = 2; k <= n2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+          for (int i = threadIdx.x; i < n2; i += 1024) {
+            const int p = i ^ j;
+            if (p > i) {
+              const int x = lst[i], y = lst[p];
+              const bool up = (i & k) == 0;
+              if ((x > y) == up) { lst[i] = y; lst[p] = x; }
+            }
+          }
+          __syncthreads();
+        }
+      for (int i = threadIdx.x; i < L; i += 1024) list[first + i] = lst[i];
+    } else {
+      int rank = 0;
+      for (int base = 0; base < T; base += kEmbSortMax) {
+        __syncthreads();
+        for (int w = threadIdx.x; w < kEmbSortMax / 32; w += 1024) bits[w] = 0u;
+        __syncthreads();
+        for (int k = threadIdx.x; k < kEmbSortMax; k += 1024)
+          if (base + k < T && ids[base + k] == id) atomicOr(&bits[k >> 5], 1u << (k & 31));
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          int run = 0;
+          for (int w = 0; w < kEmbSortMax / 32; ++w) { wpre[w] = run; run += __builtin_popcount(bits[w]); }
+          wpre[kEmbSortMax / 32] = run;
+        }
+        __syncthreads();
+        for (int w = threadIdx.x; w < kEmbSortMax / 32; w += 1024) {
+          unsigned m = bits[w];
+          int o = first + rank + wpre[w];
+          while (m) { list[o++] = base + w * 32 + __builtin_ctz(m); m &= m - 1; }
+        }
+        rank += wpre[kEmbSortMax / 32];
       }
     }
   }
 }
 
+// Sums the rows of every id on the heavy list, whose token lists are sorted by now.  grid (workgroups,
+// column splits of 128 columns); a workgroup is 16 column vectors x 16 row groups: the row of rank r goes
+// to partial sum r % 16 (each summed in ascending token order), and the 16 partial sums are combined
+// pairwise in a fixed order.
+__global__ __launch_bounds__(256) void embed_sum_kernel(const bf16_t* __restrict__ dx0, const int* __restrict__ count,
+                                                        const int* __restrict__ start, const int* __restrict__ list,
+                                                        const int* __restrict__ heavy, const int* __restrict__ n_heavy,
+                                                        bf16_t* __restrict__ dtable, int D) {
+  __shared__ float part[16][kEmbVecPerBlock][8];
+  const int vec = threadIdx.x & (kEmbVecPerBlock - 1), grp = threadIdx.x / kEmbVecPerBlock;
+  const int cvec = blockIdx.y * kEmbVecPerBlock + vec;
+  const bool col_ok = cvec < (D >> 3);
+  const int nh = *n_heavy;
+  for (int hi = blockIdx.x; hi < nh; hi += gridDim.x) {
+    const int64_t id = heavy[hi];
+    const int* lst = list + start[id];
+    const int L = count[id];
+    float a[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = 0.f;
+    if (col_ok) {
+      const bf16_t* col = dx0 + cvec * 8;
+      int j = grp;
+      for (; j + 112 < L; j += 128) {   // eight rows in flight
+        bf16x8 r[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) r[q] = *reinterpret_cast<const bf16x8*>(col + (int64_t)lst[j + 16 * q] * D);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) a[e] += (float)r[q][e];
+      }
+      for (; j < L; j += 16) {
+        const bf16x8 r0 = *reinterpret_cast<const bf16x8*>(col + (int64_t)lst[j] * D);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] += (float)r0[e];
+      }
+    }
+    __syncthreads();   // the previous id's partial sums have been read
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[grp][vec][e] = a[e];
+    __syncthreads();
+    if (grp == 0 && col_ok) {
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float q[16];
+#pragma unroll
+        for (int g = 0; g < 16; ++g) q[g] = part[g][vec][e];
+#pragma unroll
+        for (int w = 1; w < 16; w <<= 1)
+#pragma unroll
+          for (int g = 0; g < 16; g += 2 * w) q[g] += q[g + w];
+        o[e] = (bf16_t)q[0];
+      }
+      *reinterpret_cast<bf16x8*>(dtable + id * D + cvec * 8) = o;
+    }
+  }
+}
+
+// count[V], fill[V], the heavy-id counter and the segment cursor (padded to 4 ints), start[V], list[T], slot[T],
+// heavy[T / 5 + 1]
+size_t embed_bwd_workspace(int64_t T, int64_t V) { return (size_t)(3 * V + 4 + 2 * T + T / (kEmbLight + 1) + 1) * sizeof(int); }
+
 int launch_embed_bwd(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D,
-                     void* dtable, hipStream_t st) {
-  const int64_t nvec = V * D / 8;
-  hipLaunchKernelGGL(zero_kernel, dim3(ew_blocks(nvec)), dim3(256), 0, st, (u32x4*)dtable, nvec);
-  int rc = check_launch("embed_backward(zero)");
-  if (rc) return rc;
-  hipLaunchKernelGGL(embed_bwd_kernel, dim3((unsigned)T), dim3(256), 0, st, (const bf16_t*)dx0, ids,
-                     (bf16_t*)dtable, T, V, (int)D);
+                     void* dtable, void* workspace, hipStream_t st) {
+  int* count = (int*)workspace;
+  int* fill = count + V;
+  int* n_heavy = fill + V;
+  int* start = n_heavy + 4;
+  int* list = start + V;
+  int* slot = list + T;
+  int* heavy = slot + T;
+  const unsigned tb = (unsigned)((T + 255) / 256);
+  const int64_t zn = 2 * V + 4, zb = (zn + 255) / 256;
+  hipLaunchKernelGGL(embed_zero_ints_kernel, dim3((unsigned)(zb < 2048 ? zb : 2048)), dim3(256), 0, st, count, zn);
+  if (int rc = check_launch("embed_backward(clear)")) return rc;
+  hipLaunchKernelGGL(embed_count_kernel, dim3(tb), dim3(256), 0, st, ids, (int)T, V, count);
+  if (int rc = check_launch("embed_backward(count)")) return rc;
+  hipLaunchKernelGGL(embed_segments_kernel, dim3((unsigned)((V + 255) / 256)), dim3(256), 0, st, (const int*)count, start, (int)V,
+                     n_heavy + 1);
+  if (int rc = check_launch("embed_backward(segments)")) return rc;
+  hipLaunchKernelGGL(embed_fill_kernel, dim3(tb), dim3(256), 0, st, ids, (int)T, V, (const int*)count, (const int*)start, fill,
+                     list, slot, heavy, n_heavy);
+  if (int rc = check_launch("embed_backward(fill)")) return rc;
+  hipLaunchKernelGGL(embed_zero_rows_kernel, dim3((unsigned)(V < 16384 ? V : 16384)), dim3(256), 0, st, (const int*)count,
+                     (u32x4*)dtable, V, (int)(D / 8));
+  if (int rc = check_launch("embed_backward(zero)")) return rc;
+  hipLaunchKernelGGL(embed_sum_light_kernel, dim3((unsigned)T), dim3(256), 0, st, (const bf16_t*)dx0, ids, (const int*)count,
+                     (const int*)start, (const int*)list, (const int*)slot, (bf16_t*)dtable, (int)T, V, (int)D);
+  if (int rc = check_launch("embed_backward(light)")) return rc;
+  const unsigned cs = (unsigned)((D / 8 + kEmbVecPerBlock - 1) / kEmbVecPerBlock);
+  const int64_t max_heavy = T / (kEmbLight + 1) + 1;
+  hipLaunchKernelGGL(embed_sort_kernel, dim3((unsigned)(max_heavy < 1024 ? max_heavy : 1024)), dim3(1024), 0, st, ids,
+                     (const int*)count, (const int*)start, list, (const int*)heavy, (const int*)n_heavy, (int)T);
+  if (int rc = check_launch("embed_backward(sort)")) return rc;
+  hipLaunchKernelGGL(embed_sum_kernel, dim3((unsigned)(max_heavy < 256 ? max_heavy : 256), cs), dim3(256), 0, st,
+                     (const bf16_t*)dx0, (const int*)count, (const int*)start, (const int*)list, (const int*)heavy,
+                     (const int*)n_heavy, (bf16_t*)dtable, (int)D);
   return check_launch("embed_backward");
 }
 

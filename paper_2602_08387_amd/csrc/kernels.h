@@ -39,8 +39,9 @@ struct TransposeJob { const void* in; void* out; int64_t R, C, ld_out; };
 int launch_transpose_group(const TransposeJob* jobs, int n, hipStream_t st);
 int launch_embed_fwd(const void* table, const int64_t* ids, int64_t T, int64_t V, int64_t D,
                      void* x0, hipStream_t st);
+size_t embed_bwd_workspace(int64_t T, int64_t V);
 int launch_embed_bwd(const void* dx0, const int64_t* ids, int64_t T, int64_t V, int64_t D,
-                     void* dtable, hipStream_t st);
+                     void* dtable, void* workspace, hipStream_t st);
 
 // ---- gemm.hip
 // C[M,N] (bf16, row-major, leading dimension ldc) = sum over segments s of opA_s * opB_s

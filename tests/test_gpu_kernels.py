@@ -454,15 +454,23 @@ def test_ce_zero_logits_gives_log_vocab(K):
 
 
 # ------------------------------------------------------------------ embedding
-@pytest.mark.parametrize("V,D,T", [
-    (1000, 256, 700),
-    (50, 64, 20000),        # every row summed over ~400 tokens spread over three scan segments of 8192
-    (3000, 4096, 1024),     # the widest row: two column vectors per thread
-    (128256, 512, 8192),    # vocabulary and token count of the stack workload, uniform ids
+@pytest.mark.parametrize("V,D,T,dist", [
+    (1000, 256, 700, "uniform"),
+    (50, 64, 20000, "uniform"),       # every row summed over ~400 tokens
+    (3000, 4096, 1024, "uniform"),    # eight column splits per id
+    (128256, 512, 8192, "uniform"),   # vocabulary and token count of the stack workload
+    (128256, 512, 8192, "zipf"),      # text-like id frequencies: the commonest id holds some 15 % of the tokens
+    (64, 72, 40000, "one"),           # 30000 tokens on one id: more than the LDS sort holds, the id is walked instead
 ])
-def test_embedding_forward_backward(K, V, D, T):
+def test_embedding_forward_backward(K, V, D, T, dist):
     rng = np.random.default_rng(9)
-    ids = rng.integers(0, V, T)
+    if dist == "zipf":
+        ids = np.minimum(rng.zipf(1.2, T) - 1, V - 1).astype(np.int64)
+    elif dist == "one":
+        ids = rng.integers(0, V, T)
+        ids[rng.permutation(T)[:30000]] = 5
+    else:
+        ids = rng.integers(0, V, T)
     ids[:50] = 7          # heavy duplicate
     ids[T - 100:] = ids[100:200]
     Eb, db = _rand_bits(rng, (V, D), 0.02), _rand_bits(rng, (T, D))
@@ -472,13 +480,14 @@ def test_embedding_forward_backward(K, V, D, T):
     assert torch.equal(x0.view(torch.int16), Ed[idd].view(torch.int16))
     del Ed, x0
     dE = torch.full((V, D), float("nan"), dtype=torch.bfloat16, device="cuda")
-    K.embed_backward(dd, idd, T, V, D, dE)
+    ws = torch.full((K.embed_backward_workspace_bytes(T, V),), 0xFF, dtype=torch.uint8, device="cuda")
+    K.embed_backward(dd, idd, T, V, D, dE, ws)
     ref = olm.embed_bwd(si.bf16_bits_to_f64(db), ids, V)
     assert_close(dE, ref, "dE", rel_tol=6e-3)
     absent = np.setdiff1d(np.arange(V), ids)
     assert np.all(host_f64(dE)[absent] == 0)
     dE2 = torch.full((V, D), float("nan"), dtype=torch.bfloat16, device="cuda")
-    K.embed_backward(dd, idd, T, V, D, dE2)
+    K.embed_backward(dd, idd, T, V, D, dE2, ws)
     assert torch.equal(dE.view(torch.int16), dE2.view(torch.int16)), "scatter-add is not run-to-run bitwise stable"
 
 

@@ -66,7 +66,7 @@ def run_stack(K, cfg, raw, V, grad_scale=1.0, keep_rows=None, head_chunk_rows=No
         K.dlayer_backward(cfg, xs[l], W[l], dx, saved[l], dx_prev, dW[l], 0, ws)
         dx = dx_prev
     dE = bf(V, D)
-    K.embed_backward(dx, ids, T, V, D, dE)
+    K.embed_backward(dx, ids, T, V, D, dE, _buf(K.embed_backward_workspace_bytes(T, V)))
     torch.cuda.synchronize()
     return {"loss": loss.item(), "dx0": dx, "embed": dE, "w_lm": dw_lm, "g_final": dg_f, "layers": dW, "y": xs[L],
             "logits_prefix": logits_prefix}
