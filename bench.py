@@ -47,9 +47,9 @@ def _describe(cfg):
             f"{cfg.head_dim} F{cfg.d_ff} rope_base {cfg.rope_base:g}, fwd+bwd")
 
 
-def cpu_baseline(cfg, budget_tokens):
+def cpu_baseline(cfg, budget_tokens, whole=False):
     """The fp64 oracle, as it stands, on a bounded sample: the same layer (same weights and widths)
-    on one batch row cut to `budget_tokens` positions."""
+    on one batch row cut to `budget_tokens` positions; whole=True: on the whole workload."""
     import numpy as np
     from oracle import decoder_layer as odl
     from synth import inputs as si
@@ -58,7 +58,7 @@ def cpu_baseline(cfg, budget_tokens):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    sub = cfg.with_(batch=1, seq=min(cfg.seq, budget_tokens))
+    sub = cfg if whole else cfg.with_(batch=1, seq=min(cfg.seq, budget_tokens))
     inp = si.to_f64(si.make_layer_inputs(sub, seed=0))
     x, dy = inp.pop("x"), inp.pop("dy")
     t0 = time.perf_counter()
@@ -68,8 +68,8 @@ def cpu_baseline(cfg, budget_tokens):
     flops = si.layer_fwd_bwd_flops(sub)
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
             "seconds": dt, "tokens_per_s": sub.tokens / dt,
-            "sample": f"same layer and weights, 1 batch row cut to {sub.seq} positions "
-                      f"({sub.tokens} of {cfg.tokens} tokens), fp64 NumPy, fwd+bwd"}
+            "sample": ("the whole workload" if whole else f"same layer and weights, 1 batch row cut to {sub.seq} positions") +
+                      f" ({sub.tokens} of {cfg.tokens} tokens), fp64 NumPy, fwd+bwd"}
 
 
 def bench_stack(args, torch, K, si, dev_bf16):
@@ -133,6 +133,78 @@ def bench_stack(args, torch, K, si, dev_bf16):
         "loss": float(loss.item())}))
 
 
+def time_components(torch, K, si, cfg, x, w, reps):
+    """The pieces of one step, each launched on its own through the building-block entry point that
+    dlayer_forward / dlayer_backward use for it (same kernels, same shapes), one event pair per launch
+    on the launch stream.  Returns a list of rows: name, kernel, ms, algorithmic TFLOP (or GB for the
+    HBM-bound ones), achieved rate and its fraction of the bf16 MFMA peak (or of 8 TB/s)."""
+    B, S, T, D, F = cfg.batch, cfg.seq, cfg.tokens, cfg.d_model, cfg.d_ff
+    Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    QD, KD = Hq * dh, Hkv * dh
+    bf = lambda *shape: torch.empty(*shape, dtype=torch.bfloat16, device="cuda").normal_()
+    u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device="cuda")
+    h, q, k, v, o = bf(T, D), bf(T, QD), bf(T, KD), bf(T, KD), bf(T, QD)
+    g, u, a, y = bf(T, F), bf(T, F), bf(T, F), bf(T, D)
+    dq, dk, dv, dg, du = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v), torch.empty_like(g), torch.empty_like(u)
+    dx = torch.empty_like(h)
+    lse = torch.empty(B, Hq, S, dtype=torch.float32, device="cuda")
+    rstd = torch.empty(T, dtype=torch.float32, device="cuda")
+    dgam = torch.empty(D, dtype=torch.bfloat16, device="cuda")
+    dws = {n: torch.empty_like(t) for n, t in w.items() if t.dim() == 2}
+    ws_rope, ws_attn = u8(K.qkv_rope_workspace_bytes(S, dh)), u8(K.attention_backward_workspace_bytes(B, S, Hq, Hkv, dh))
+    ws_sw, ws_norm = u8(K.linear_swiglu_backward_workspace_bytes(T, D, F)), u8(K.rmsnorm_backward_workspace_bytes(T, D))
+    ws_lin = u8(K.linear_backward_workspace_bytes(T, F, D))
+    attn = 2.0 * B * Hq * float(S) ** 2 * dh
+    wg = [("w_down", x, a, D, F), ("w_gate", dg, h, F, D), ("w_up", du, h, F, D), ("wo", x, o, D, QD),
+          ("wq", dq, h, QD, D), ("wk", dk, h, KD, D), ("wv", dv, h, KD, D)]
+    K.attention_forward(q, k, v, B, S, Hq, Hkv, dh, o, lse)     # a valid lse for the backward launches
+    rows = [
+        ("q, k, v projections + RoPE", "gemm_group_rope_kernel", 2.0 * T * D * (QD + 2 * KD),
+         lambda: K.qkv_rope_forward(h, w["wq"], w["wk"], w["wv"], B, S, D, Hq, Hkv, dh, cfg.rope_base, cfg.rope_layout, q, k, v, ws_rope)),
+        ("attention forward", "attn_fwd_kernel", attn, lambda: K.attention_forward(q, k, v, B, S, Hq, Hkv, dh, o, lse)),
+        ("o projection + residual", "gemm_kernel<k,k>", 2.0 * T * QD * D, lambda: K.linear_forward(o, w["wo"], x, T, QD, D, y)),
+        ("gate/up projections + SwiGLU", "gemm_swiglu_kernel<1>", 4.0 * T * D * F,
+         lambda: K.linear_swiglu_forward(h, w["w_gate"], w["w_up"], T, D, F, g, u, a)),
+        ("down projection + residual", "gemm_kernel<k,k>", 2.0 * T * F * D, lambda: K.linear_forward(a, w["w_down"], x, T, F, D, y)),
+        ("down input gradient + SwiGLU gradient (+ W_down transpose)", "gemm_swiglu_kernel<2>", 2.0 * T * D * F,
+         lambda: K.linear_swiglu_backward(x, w["w_down"], g, u, T, D, F, dg, du, ws_sw)),
+        ("gate input gradient (+ W_gate transpose)", "gemm_kernel<k,k>", 2.0 * T * D * F,
+         lambda: K.linear_backward(h, w["w_gate"], dg, T, D, F, dx, None, 0, ws_lin)),
+        ("o input gradient (+ W_o transpose)", "gemm_kernel<k,k>", 2.0 * T * QD * D,
+         lambda: K.linear_backward(o, w["wo"], x, T, QD, D, dq, None, 0, ws_lin)),
+        ("attention backward (delta, dV, dK, dQ)", "attn_delta + attn_bwd_dkv x2 + attn_bwd_dq", 2.0 * attn,
+         lambda: K.attention_backward(q, k, v, o, dq, lse, B, S, Hq, Hkv, dh, dq, dk, dv, ws_attn)),
+        ("seven weight gradients, one launch", "gemm_group_kernel<mn,mn>", sum(2.0 * T * N * Kd for _, _, _, N, Kd in wg),
+         lambda: K.linear_wgrad_group([d for _, d, _, _, _ in wg], [xx for _, _, xx, _, _ in wg], [N for *_, N, _ in wg],
+                                      [Kd for *_, Kd in wg], T, [dws[n] for n, *_ in wg], 0)),
+    ]
+    hbm = [
+        ("RMSNorm forward", "rmsnorm_fwd_kernel", 4.0 * T * D, lambda: K.rmsnorm_forward(x, w["g_attn"], T, D, cfg.rms_eps, h, rstd)),
+        ("RMSNorm backward + residual gradient", "rmsnorm_bwd_kernel", 10.0 * T * D,
+         lambda: K.rmsnorm_backward(x, w["g_attn"], rstd, h, y, T, D, dx, dgam, 0, ws_norm)),
+    ]
+    K.rmsnorm_forward(x, w["g_attn"], T, D, cfg.rms_eps, h, rstd)
+    out = []
+    for kind, table in (("mfma", rows), ("hbm", hbm)):
+        for name, kernel, work, fn in table:
+            fn()
+            evs = []
+            for _ in range(reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); fn(); e1.record()
+                evs.append((e0, e1))
+            torch.cuda.synchronize()
+            ms = sum(p.elapsed_time(q_) for p, q_ in evs) / reps
+            if kind == "mfma":
+                rate = work / (ms * 1e-3) / 1e12
+                out.append({"name": name, "kernel": kernel, "bound": "mfma", "ms": ms, "tflop": work / 1e12, "tflops": rate,
+                            "frac": rate / PEAK_BF16_TFLOPS})
+            else:
+                rate = work / (ms * 1e-3) / 1e9
+                out.append({"name": name, "kernel": kernel, "bound": "hbm", "ms": ms, "gb": work / 1e9, "gbps": rate, "frac": rate / 8000.0})
+    return out
+
+
 def bench_optimizer(args, torch, K, si):
     """The optimizer step of one 8B-shaped layer (not the headline line): global-norm clipping and AdamW
     over the layer's nine parameter tensors (218 M bf16 parameters, fp32 moments).  Both kernels are
@@ -182,6 +254,9 @@ def main():
     ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b", "70b_width", "stack", "optimizer"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=4096)
+    ap.add_argument("--cpu-full", action="store_true",
+                    help="also run the oracle once over the whole workload (about two minutes of host time at the 8B shape)")
+    ap.add_argument("--no-components", action="store_true", help="skip the per-piece timing table")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size dispatch that HBM byte "
                          "counters of a profiler run are scaled by)")
@@ -194,7 +269,7 @@ def main():
     import torch
     import paper_2602_08387_amd as K   # raises if the HIP library is not built: no fallback
     from synth import inputs as si
-    from tests.parity import dev_bf16
+    from synth.device import dev_bf16
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -306,8 +381,19 @@ def main():
         "paper_throughput": "not reported in the paper's text (Fig. 2b is an image; 8B Llama-3, Leonardo)",
         "roofline": roofline,
     }
+    if not args.no_components:
+        # every piece of the step on its own: which kernel is dominant in the step, which one is furthest
+        # from its roofline
+        comps = time_components(torch, K, si, cfg, x.view(T, D), w, max(3, min(10, args.steps)))
+        mf = [c for c in comps if c["bound"] == "mfma"]
+        roofline["in_step"] = comps
+        roofline["in_step_sum_ms"] = sum(c["ms"] for c in comps)
+        roofline["in_step_dominant"] = max(mf, key=lambda c: c["ms"])["name"]
+        roofline["in_step_worst"] = min(mf, key=lambda c: c["frac"])["name"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_tokens)
+        if args.cpu_full:
+            out["cpu_baseline_full"] = cpu_baseline(cfg, cfg.seq, whole=True)
     print(json.dumps(out))
 
 

@@ -32,7 +32,7 @@
  *     multiple of 128; every contraction (inner) dimension a multiple of 64 (for a layer:
  *     d_model, d_ff, n_q_heads*head_dim, n_kv_heads*head_dim and batch*seq) and every output
  *     feature dimension a multiple of 8; d_model <= 16384; feature counts of the element-wise
- *     kernels a multiple of 8; every tensor smaller than 4 GiB.
+ *     kernels a multiple of 8; every tensor, activation or weight, smaller than 4 GiB.
  */
 #ifndef DLAYER_H
 #define DLAYER_H
@@ -92,12 +92,22 @@ int dlayer_forward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w
 /*
  * Backward of dlayer_forward for upstream gradient dy [T, D] bf16: writes dx [T, D] bf16 and
  * the nine parameter gradients (each summed over all T tokens; fp32 accumulation, bf16
- * result).  accumulate_wgrads = 0 overwrites the gradient tensors; 1 adds to their current
- * contents.  x, w and saved must be those of the matching forward call.
+ * result).  x, w and saved must be those of the matching forward call.  flags (0 or an OR of):
+ *   DLAYER_ACCUMULATE_WGRADS         add to the current contents of the gradient tensors instead of
+ *                                    overwriting them;
+ *   DLAYER_REUSE_TRANSPOSED_WEIGHTS  the input-gradient products read transposed copies of the seven
+ *                                    weight matrices, written into `workspace` at the start of every
+ *                                    call; with this flag the call trusts that the copies a previous
+ *                                    dlayer_backward left there - same cfg, same weight VALUES, same
+ *                                    workspace, nothing else having written to it since
+ *                                    (dlayer_forward does not) - are still valid and skips rewriting
+ *                                    them: for several micro-batches between two optimizer steps.
  */
+#define DLAYER_ACCUMULATE_WGRADS 1
+#define DLAYER_REUSE_TRANSPOSED_WEIGHTS 2
 int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w,
                     const void* dy, const void* saved, void* dx, const dlayer_wgrads* dw,
-                    int accumulate_wgrads, void* workspace, void* stream);
+                    int flags, void* workspace, void* stream);
 
 /*
  * Mean softmax cross-entropy over T rows of V logits and its gradient (training loss of the

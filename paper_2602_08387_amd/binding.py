@@ -22,6 +22,10 @@ EXPORTED_SYMBOLS = (
 )
 
 
+DLAYER_ACCUMULATE_WGRADS = 1
+DLAYER_REUSE_TRANSPOSED_WEIGHTS = 2
+
+
 class DLayerError(RuntimeError):
     pass
 
@@ -145,9 +149,9 @@ def dlayer_forward(cfg, x, weights, y, saved, workspace, stream=None):
                               _p(saved), _p(workspace), _stream(stream)), "dlayer_forward")
 
 
-def dlayer_backward(cfg, x, weights, dy, saved, dx, wgrads, accumulate_wgrads, workspace, stream=None):
+def dlayer_backward(cfg, x, weights, dy, saved, dx, wgrads, flags, workspace, stream=None):
     _check(lib.dlayer_backward(C.byref(LayerCfg.of(cfg)), _p(x), C.byref(_ptr_struct(weights)), _p(dy),
-                               _p(saved), _p(dx), C.byref(_ptr_struct(wgrads)), int(accumulate_wgrads),
+                               _p(saved), _p(dx), C.byref(_ptr_struct(wgrads)), int(flags),
                                _p(workspace), _stream(stream)), "dlayer_backward")
 
 

@@ -79,6 +79,10 @@ static const char* cfg_problem(const dlayer_cfg* c) {
   const int64_t widest = padded_ff(c) > c->n_q_heads * c->head_dim ? padded_ff(c) : (int64_t)c->n_q_heads * c->head_dim;
   if (T * widest * 2 >= ((int64_t)1 << 32) || T * c->d_model * 2 >= ((int64_t)1 << 32))
     return "an activation tensor reaches 4 GiB";
+  // the weights (and their transposed copies, whose d_ff rows are padded) are addressed with 32-bit byte offsets too
+  const int64_t D = c->d_model, QD = (int64_t)c->n_q_heads * c->head_dim;
+  if (padded_ff(c) * D * 2 >= ((int64_t)1 << 32) || QD * D * 2 >= ((int64_t)1 << 32))
+    return "a weight tensor reaches 4 GiB";
   return nullptr;
 }
 
@@ -254,11 +258,12 @@ int dlayer_forward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w
 }
 
 int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w, const void* dy,
-                    const void* saved, void* dx, const dlayer_wgrads* dw, int accumulate_wgrads,
+                    const void* saved, void* dx, const dlayer_wgrads* dw, int flags,
                     void* workspace, void* stream) {
   const char* prob = cfg_problem(cfg);
   REQUIRE(!prob, "dlayer_backward: %s", prob);
   REQUIRE(w != nullptr && dw != nullptr, "dlayer_backward: weights or gradient struct is null");
+  REQUIRE((flags & ~(DLAYER_ACCUMULATE_WGRADS | DLAYER_REUSE_TRANSPOSED_WEIGHTS)) == 0, "dlayer_backward: unknown flag bits 0x%x", flags);
   REQUIRE_PTR(x); REQUIRE_PTR(dy); REQUIRE_PTR(saved); REQUIRE_PTR(dx); REQUIRE_PTR(workspace);
   REQUIRE_PTR(w->g_attn); REQUIRE_PTR(w->wq); REQUIRE_PTR(w->wk); REQUIRE_PTR(w->wv); REQUIRE_PTR(w->wo);
   REQUIRE_PTR(w->g_mlp); REQUIRE_PTR(w->w_gate); REQUIRE_PTR(w->w_up); REQUIRE_PTR(w->w_down);
@@ -266,13 +271,13 @@ int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* 
   REQUIRE_PTR(dw->g_mlp); REQUIRE_PTR(dw->w_gate); REQUIRE_PTR(dw->w_up); REQUIRE_PTR(dw->w_down);
   TRY(check_device());
   hipStream_t st = (hipStream_t)stream;
-  const int acc = accumulate_wgrads ? 1 : 0;
+  const int acc = (flags & DLAYER_ACCUMULATE_WGRADS) ? 1 : 0;
   const int64_t B = cfg->batch, S = cfg->seq, T = B * S, D = cfg->d_model, F = cfg->d_ff;
   const int64_t Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, dh = cfg->head_dim, QD = Hq * dh, KD = Hkv * dh;
   Saved s = carve_saved(cfg, const_cast<void*>(saved));
   Work k = carve_work(cfg, workspace);
   const int64_t Fp = padded_ff(cfg);
-  {
+  if (!(flags & DLAYER_REUSE_TRANSPOSED_WEIGHTS)) {
     const TransposeJob jobs[7] = {{w->w_down, k.wdT, D, F, D},  {w->w_gate, k.wgT, F, D, Fp}, {w->w_up, k.wuT, F, D, Fp},
                                   {w->wo, k.woT, D, QD, D},     {w->wq, k.wqT, QD, D, QD},    {w->wk, k.wkT, KD, D, KD},
                                   {w->wv, k.wvT, KD, D, KD}};

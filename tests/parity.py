@@ -4,14 +4,10 @@ import numpy as np
 import torch
 
 from synth import inputs as si
+from synth.device import dev_bf16, host_f64  # noqa: F401  (re-exported for the tests)
 
 REL_TOL = 2e-2      # max |gpu - ref| / max(|ref|, rms(ref)) on outputs
 COS_TOL = 0.999     # cosine similarity per gradient tensor
-
-
-def dev_bf16(bits: np.ndarray) -> torch.Tensor:
-    """uint16 bf16 bit patterns -> torch.bfloat16 tensor on the GPU (same bits)."""
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
 
 
 def f64_to_bf16_bits(a: np.ndarray) -> np.ndarray:
@@ -26,12 +22,6 @@ def dev_from_f64(a: np.ndarray) -> torch.Tensor:
 def rounded(a: np.ndarray) -> np.ndarray:
     """The fp64 value of `a` after rounding to bf16."""
     return si.bf16_bits_to_f64(f64_to_bf16_bits(a))
-
-
-def host_f64(t: torch.Tensor) -> np.ndarray:
-    if t.dtype == torch.bfloat16:
-        return si.bf16_bits_to_f64(t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16))
-    return t.detach().cpu().numpy().astype(np.float64)
 
 
 def rel_err(got: np.ndarray, ref: np.ndarray) -> float:

@@ -103,6 +103,27 @@ def test_layer_large_scores_and_accumulate(K):
         assert_close(g.dw[n], 2 * r[n], f"acc:d{n}", rel_tol=np.inf)
 
 
+def test_backward_can_reuse_the_transposed_weights(K):
+    """Two micro-batches through one layer: the second backward is told that the transposed weight
+    copies the first one left in the workspace are still valid (the forward in between does not touch
+    them) and must give, bit for bit, what a backward that rewrites them gives."""
+    cfg = si.CONFIGS["small"].with_(batch=2)
+    a_in, b_in = si.make_layer_inputs(cfg, seed=8), si.make_layer_inputs(cfg, seed=9)
+    b_in.update({n: a_in[n] for n in si.WEIGHT_NAMES})          # same weights, new activations
+    g = GpuLayer(K, cfg, a_in)
+    g.forward(); g.backward()
+    g.x.copy_(dev_bf16(b_in["x"])); g.dy.copy_(dev_bf16(b_in["dy"]))
+    g.forward(); g.backward(accumulate=2)                       # DLAYER_REUSE_TRANSPOSED_WEIGHTS
+    torch.cuda.synchronize()
+    ref = GpuLayer(K, cfg, b_in)
+    ref.forward(); ref.backward()
+    torch.cuda.synchronize()
+    for name, p, q in [("dx", g.dx, ref.dx)] + [(n, g.dw[n], ref.dw[n]) for n in si.WEIGHT_NAMES]:
+        assert torch.equal(p.view(torch.int16), q.view(torch.int16)), f"{name} differs when the transposed weights are reused"
+    with pytest.raises(K.DLayerError, match="unknown flag"):
+        g.backward(accumulate=8)
+
+
 def test_layer_is_causal_and_deterministic(K):
     cfg = si.CONFIGS["tiny"].with_(seq=256, batch=2)
     inp = si.make_layer_inputs(cfg, seed=1)
