@@ -6,7 +6,8 @@ import torch
 
 from oracle import decoder_layer as odl
 from synth import inputs as si
-from tests.parity import COS_TOL, REL_TOL, assert_close, cosine, dev_bf16, host_f64, rel_err
+from tests.parity import (COS_TOL, REL_TOL, assert_close, cosine, dev_bf16, f64_to_bf16_bits, host_f64, rel_err,
+                          rounded)
 
 pytestmark = pytest.mark.gpu
 
@@ -242,3 +243,93 @@ def test_8b_shape_prefix_parity(K):
     for n in si.WEIGHT_NAMES:
         rep[n] = assert_close(g.dw[n], r[n], f"8b:d{n}", rel_tol=np.inf)
     print("8b", {k: (f"{a:.2e}", f"{b:.6f}") for k, (a, b) in rep.items()})
+    # Floor or defect?  The same forward evaluated in fp64 but rounded to bf16 exactly where the library
+    # stores a tensor (h1, rotated q and k, v, o, y1, h2, a, y).  Step by step the kernels reproduce that
+    # evaluation bit for bit on 99.95 % of the elements (test_8b_width_steps_against_the_storage_emulation);
+    # the one thing it leaves out is the bf16 rounding of the softmax weights inside the attention kernel,
+    # which alone moves o by up to 1.2e-2 on this metric, so the whole layer sits as far from the emulation
+    # (measured 2.06e-2) as the emulation sits from the exact result (2.48e-2): same noise, other draw.
+    v = {k: si.bf16_bits_to_f64(inp[k]) for k in si.WEIGHT_NAMES}
+    x64 = si.bf16_bits_to_f64(sub_inp["x"])
+    Bq, S, D = x64.shape
+    Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    h1 = rounded(odl.rmsnorm_fwd(x64, v["g_attn"], cfg.rms_eps)[0])
+    phi = odl.rope_angles(S, dh, cfg.rope_base)
+    q = rounded(odl.rope_rotate((h1 @ v["wq"].T).reshape(Bq, S, Hq, dh), phi))
+    k = rounded(odl.rope_rotate((h1 @ v["wk"].T).reshape(Bq, S, Hkv, dh), phi))
+    vv = rounded((h1 @ v["wv"].T).reshape(Bq, S, Hkv, dh))
+    o = rounded(odl.attention_fwd(q, k, vv)[0])
+    y1 = rounded(x64 + o.reshape(Bq, S, Hq * dh) @ v["wo"].T)
+    h2 = rounded(odl.rmsnorm_fwd(y1, v["g_mlp"], cfg.rms_eps)[0])
+    a = rounded(odl.swiglu_fwd(h2 @ v["w_gate"].T, h2 @ v["w_up"].T))
+    y_emu = rounded(y1 + a @ v["w_down"].T)
+    r_emu = rel_err(host_f64(g.y[:, :P]), y_emu)
+    print(f"8b:y against the bf16-storage emulation: rel_err {r_emu:.3e}")
+    assert r_emu <= 2.2e-2, r_emu
+
+
+def test_8b_width_steps_against_the_storage_emulation(K):
+    """Each step of the forward at the 8B widths, fed with the tensor the fp64 evaluation holds at that
+    point after rounding it to bf16 where the library stores it: the step's output must equal the fp64
+    result rounded to bf16 except where the fp32 sum lands on the other side of a rounding boundary,
+    i.e. be bit-identical almost everywhere and never more than one bf16 step away.  This separates the
+    rounding floor of bf16 storage from any defect of a kernel."""
+    cfg = si.CONFIGS["8b"].with_(batch=1, seq=512)   # 512 rows: enough tiles for the fused gate/up kernel
+    inp = si.make_layer_inputs(cfg, seed=0)
+    w = {k: si.bf16_bits_to_f64(inp[k]) for k in si.WEIGHT_NAMES}
+    wd = {k: dev_bf16(inp[k]) for k in si.WEIGHT_NAMES}
+    x = si.bf16_bits_to_f64(inp["x"])[0]
+    T, D, F = cfg.tokens, cfg.d_model, cfg.d_ff
+    Hq, Hkv, dh, S = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.seq
+    QD, KD = Hq * dh, Hkv * dh
+    up = lambda a: dev_bf16(f64_to_bf16_bits(a))
+    bf = lambda *s: torch.full(s, float("nan"), dtype=torch.bfloat16, device="cuda")
+    report = {}
+
+    def check(name, got, ref64, min_exact):
+        ref = rounded(ref64)
+        got = host_f64(got).reshape(ref.shape)
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)
+        exact = float(np.mean(got == ref))
+        # where terms cancel the fp32 rounding of the terms shows next to a tiny result: 1e-5 of the
+        # tensor's rms is allowed on top of the one rounding step
+        slack = 1e-5 * np.sqrt(np.mean(ref * ref))
+        worst = float(np.max(np.maximum(np.abs(got - ref) - slack, 0.0) / ulp))
+        report[name] = (exact, worst)
+        assert exact >= min_exact and worst <= 1.001, (name, exact, worst)
+        return ref
+
+    h1g, rstd = bf(T, D), torch.empty(T, dtype=torch.float32, device="cuda")
+    K.rmsnorm_forward(up(x), wd["g_attn"], T, D, cfg.rms_eps, h1g, rstd)
+    h1 = check("h1", h1g, odl.rmsnorm_fwd(x, w["g_attn"], cfg.rms_eps)[0], 0.999)
+    qg, kg, vg = bf(T, QD), bf(T, KD), bf(T, KD)
+    ws = torch.empty(K.qkv_rope_workspace_bytes(S, dh), dtype=torch.uint8, device="cuda")
+    K.qkv_rope_forward(up(h1), wd["wq"], wd["wk"], wd["wv"], 1, S, D, Hq, Hkv, dh, cfg.rope_base, 0, qg, kg, vg, ws)
+    phi = odl.rope_angles(S, dh, cfg.rope_base)
+    q = check("q", qg, odl.rope_rotate((h1 @ w["wq"].T).reshape(1, S, Hq, dh), phi), 0.995)
+    k = check("k", kg, odl.rope_rotate((h1 @ w["wk"].T).reshape(1, S, Hkv, dh), phi), 0.995)
+    v = check("v", vg, (h1 @ w["wv"].T).reshape(1, S, Hkv, dh), 0.995)
+    og, lse = bf(T, QD), torch.empty(1, Hq, S, dtype=torch.float32, device="cuda")
+    K.attention_forward(up(q), up(k), up(v), 1, S, Hq, Hkv, dh, og, lse)
+    # the attention output also carries the bf16 rounding of the softmax weights: bounded by its own
+    # per-kernel tolerance rather than by one rounding step
+    o_ref = odl.attention_fwd(q, k, v)[0]
+    report["o"] = assert_close(og, o_ref, "o", rel_tol=2.5e-2)
+    o = rounded(o_ref).reshape(T, QD)
+    y1g = bf(T, D)
+    K.linear_forward(up(o), wd["wo"], up(x), T, QD, D, y1g)
+    y1 = check("y1", y1g, x + o @ w["wo"].T, 0.995)
+    h2g = bf(T, D)
+    K.rmsnorm_forward(up(y1), wd["g_mlp"], T, D, cfg.rms_eps, h2g, rstd)
+    h2 = check("h2", h2g, odl.rmsnorm_fwd(y1, w["g_mlp"], cfg.rms_eps)[0], 0.999)
+    gg, ug, ag = bf(T, F), bf(T, F), bf(T, F)
+    K.linear_swiglu_forward(up(h2), wd["w_gate"], wd["w_up"], T, D, F, gg, ug, ag)
+    g64, u64 = h2 @ w["w_gate"].T, h2 @ w["w_up"].T
+    check("g", gg, g64, 0.995)
+    check("u", ug, u64, 0.995)
+    a = check("a", ag, odl.swiglu_fwd(g64, u64), 0.99)
+    yg = bf(T, D)
+    K.linear_forward(up(a), wd["w_down"], up(y1), T, F, D, yg)
+    check("y", yg, y1 + a @ w["w_down"].T, 0.995)
+    print("steps vs storage emulation (fraction bit-identical, worst distance in bf16 steps):",
+          {k: (f"{e:.5f}", f"{wst:.3g}") for k, (e, wst) in report.items()})
