@@ -55,7 +55,16 @@ typedef struct dlayer_cfg {
   float rms_eps;       /* added to the mean square inside the square root          */
   float rope_base;     /* rotary base: angle(p, i) = p * rope_base^(-2 i / head_dim) */
   int32_t rope_layout; /* 0: element i pairs with i + head_dim/2; 1: 2i pairs with 2i+1 */
+  int32_t recompute;   /* 0, or an OR of DLAYER_RECOMPUTE_*: activations dlayer_forward does not keep in
+                          `saved` and dlayer_backward rebuilds (they are operands of the weight gradients
+                          only).  Same cfg in the forward, the backward and the size queries.           */
 } dlayer_cfg;
+/* the two RMSNorm outputs h1, h2 [T, D]: rebuilt from x, y1 and the saved statistics                 */
+#define DLAYER_RECOMPUTE_NORMS 1
+/* the SwiGLU output a [T, d_ff]: rebuilt from the saved g and u (from their bf16 values, where the
+ * forward's fused kernel used the fp32 sums: the down-projection weight gradient sees a rounded once
+ * more)                                                                                              */
+#define DLAYER_RECOMPUTE_SWIGLU 2
 
 /* Device pointers to the nine parameter tensors of a layer (bf16):
  * g_attn [D], wq [Hq*dh, D], wk [Hkv*dh, D], wv [Hkv*dh, D], wo [D, Hq*dh],
@@ -100,7 +109,7 @@ int dlayer_forward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w
  *                                    call; with this flag the call trusts that the copies a previous
  *                                    dlayer_backward left there - same cfg, same weight VALUES, same
  *                                    workspace, nothing else having written to it since
- *                                    (dlayer_forward does not) - are still valid and skips rewriting
+ *                                    (dlayer_forward leaves that part alone) - are still valid and skips rewriting
  *                                    them: for several micro-batches between two optimizer steps.
  */
 #define DLAYER_ACCUMULATE_WGRADS 1

@@ -11,7 +11,7 @@ compiles the library) can be imported on a tree that holds no library yet.
 import importlib
 
 _BINDING_NAMES = (
-    "DLayerError", "LayerCfg", "lib", "lib_path", "DLAYER_ACCUMULATE_WGRADS", "DLAYER_REUSE_TRANSPOSED_WEIGHTS",
+    "DLayerError", "LayerCfg", "lib", "lib_path", "DLAYER_ACCUMULATE_WGRADS", "DLAYER_REUSE_TRANSPOSED_WEIGHTS", "DLAYER_RECOMPUTE_NORMS", "DLAYER_RECOMPUTE_SWIGLU",
     "dlayer_version", "dlayer_saved_bytes", "dlayer_workspace_bytes", "dlayer_forward", "dlayer_backward",
     "ce_loss_workspace_bytes", "ce_loss_fwd_bwd", "ce_loss_fwd_bwd_static", "lm_head_ce_workspace_bytes", "lm_head_ce_fwd_bwd",
     "rmsnorm_forward", "rmsnorm_backward", "rmsnorm_backward_workspace_bytes",

@@ -24,6 +24,8 @@ EXPORTED_SYMBOLS = (
 
 DLAYER_ACCUMULATE_WGRADS = 1
 DLAYER_REUSE_TRANSPOSED_WEIGHTS = 2
+DLAYER_RECOMPUTE_NORMS = 1
+DLAYER_RECOMPUTE_SWIGLU = 2
 
 
 class DLayerError(RuntimeError):
@@ -35,14 +37,14 @@ class LayerCfg(C.Structure):
     _fields_ = [("batch", C.c_int32), ("seq", C.c_int32), ("d_model", C.c_int32),
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("d_ff", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float),
-                ("rope_layout", C.c_int32)]
+                ("rope_layout", C.c_int32), ("recompute", C.c_int32)]
 
     @classmethod
     def of(cls, cfg) -> "LayerCfg":
         """Accepts a LayerCfg or any object with the same attribute names."""
         if isinstance(cfg, cls):
             return cfg
-        return cls(*(getattr(cfg, n) for n, _ in cls._fields_))
+        return cls(*(getattr(cfg, n, 0) for n, _ in cls._fields_))
 
 
 class _Ptrs(C.Structure):

@@ -74,6 +74,7 @@ static const char* cfg_problem(const dlayer_cfg* c) {
     return "n_q_heads*head_dim and n_kv_heads*head_dim must be multiples of 64";
   if (c->d_model > 16384) return "d_model above 16384 is not supported";
   if (c->rope_layout != 0 && c->rope_layout != 1) return "rope_layout must be 0 or 1";
+  if (c->recompute & ~(DLAYER_RECOMPUTE_NORMS | DLAYER_RECOMPUTE_SWIGLU)) return "unknown recompute bits";
   if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return "rms_eps must be >= 0 and rope_base > 0";
   const int64_t T = (int64_t)c->batch * c->seq;
   const int64_t widest = padded_ff(c) > c->n_q_heads * c->head_dim ? padded_ff(c) : (int64_t)c->n_q_heads * c->head_dim;
@@ -101,22 +102,23 @@ static Saved carve_saved(const dlayer_cfg* c, void* p) {
   s.lse = (float*)cv.take(T * c->n_q_heads * 4);
   s.rope_cos = (float*)cv.take((size_t)c->seq * (c->head_dim / 2) * 4);
   s.rope_sin = (float*)cv.take((size_t)c->seq * (c->head_dim / 2) * 4);
-  s.h1 = cv.take(T * D * 2);
+  s.h1 = (c->recompute & DLAYER_RECOMPUTE_NORMS) ? nullptr : cv.take(T * D * 2);
   s.q = cv.take(T * QD * 2);
   s.k = cv.take(T * KD * 2);
   s.v = cv.take(T * KD * 2);
   s.o = cv.take(T * QD * 2);
   s.y1 = cv.take(T * D * 2);
-  s.h2 = cv.take(T * D * 2);
+  s.h2 = (c->recompute & DLAYER_RECOMPUTE_NORMS) ? nullptr : cv.take(T * D * 2);
   s.g = cv.take(T * F * 2);
   s.u = cv.take(T * F * 2);
-  s.a = cv.take(T * padded_ff(c) * 2);
+  s.a = (c->recompute & DLAYER_RECOMPUTE_SWIGLU) ? nullptr : cv.take(T * padded_ff(c) * 2);
   s.bytes = cv.off;
   return s;
 }
 
 struct Work {
   void *da_dg, *du, *dh2, *dy1, *d_o, *dq, *dk, *dv, *dh1, *attn_ws, *rms_ws;
+  void *h1, *h2, *a;   // the activations a recomputing configuration does not keep in `saved` (null otherwise)
   void *wqT, *wkT, *wvT, *woT, *wgT, *wuT, *wdT;   // W^T copies: the input-gradient products then read both operands k-major
   size_t bytes;
 };
@@ -138,6 +140,9 @@ static Work carve_work(const dlayer_cfg* c, void* p) {
   w.rms_ws = cv.take(rmsnorm_bwd_workspace(T, D));
   w.wqT = cv.take(QD * D * 2); w.wkT = cv.take(KD * D * 2); w.wvT = cv.take(KD * D * 2); w.woT = cv.take(D * QD * 2);
   w.wgT = cv.take(D * padded_ff(c) * 2); w.wuT = cv.take(D * padded_ff(c) * 2); w.wdT = cv.take(D * F * 2);
+  w.h1 = (c->recompute & DLAYER_RECOMPUTE_NORMS) ? cv.take(T * D * 2) : nullptr;
+  w.h2 = (c->recompute & DLAYER_RECOMPUTE_NORMS) ? cv.take(T * D * 2) : nullptr;
+  w.a = (c->recompute & DLAYER_RECOMPUTE_SWIGLU) ? cv.take(T * padded_ff(c) * 2) : nullptr;
   w.bytes = cv.off;
   return w;
 }
@@ -238,6 +243,13 @@ int dlayer_forward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* w
   const int64_t B = cfg->batch, S = cfg->seq, T = B * S, D = cfg->d_model, F = cfg->d_ff;
   const int64_t Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, dh = cfg->head_dim, QD = Hq * dh, KD = Hkv * dh;
   Saved s = carve_saved(cfg, saved);
+  {
+    // what a recomputing configuration does not keep for the backward lives in the workspace for the
+    // length of this call
+    const Work k = carve_work(cfg, workspace);
+    if (!s.h1) { s.h1 = k.h1; s.h2 = k.h2; }
+    if (!s.a) s.a = k.a;
+  }
   TRY(launch_rmsnorm_fwd(x, w->g_attn, T, D, cfg->rms_eps, s.h1, s.rstd1, st));
   TRY(launch_rope_table(s.rope_cos, s.rope_sin, S, dh, cfg->rope_base, st));
   {
@@ -304,6 +316,17 @@ int dlayer_backward(const dlayer_cfg* cfg, const void* x, const dlayer_weights* 
     TRY(gemm_dgrad_t(3, dys, ws, ns, 0, T, D, k.dh1, D, st));
   }
   TRY(launch_rmsnorm_bwd(x, w->g_attn, s.rstd1, k.dh1, k.dy1, T, D, dx, dw->g_attn, acc, k.rms_ws, st));
+  // Recomputing configurations: the normalised activations and the SwiGLU output are only operands of
+  // the weight gradients; they are rebuilt here from x, y1 (with the saved statistics) and from g, u.
+  if (!s.h1) {
+    s.h1 = k.h1; s.h2 = k.h2;
+    TRY(launch_rmsnorm_fwd(x, w->g_attn, T, D, cfg->rms_eps, s.h1, s.rstd1, st));
+    TRY(launch_rmsnorm_fwd(s.y1, w->g_mlp, T, D, cfg->rms_eps, s.h2, s.rstd2, st));
+  }
+  if (!s.a) {
+    s.a = k.a;
+    TRY(launch_swiglu_fwd_rows(s.g, s.u, T, F, F, s.a, Fp, st));
+  }
   // All seven weight gradients in one grid: every operand (saved activations, the gradient buffers
   // of the workspace, dy) is still alive here, and one launch fills the chip evenly where the
   // separate products leave partly filled rounds (and two of them are too small to fill it at all).

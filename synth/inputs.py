@@ -32,6 +32,7 @@ class LayerConfig:
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     rope_layout: int = 0  # 0: pairs (i, i + dh/2); 1: pairs (2i, 2i+1)
+    recompute: int = 0    # library option (which activations the backward rebuilds); no effect on the mathematics
 
     @property
     def tokens(self) -> int:

@@ -125,6 +125,26 @@ def test_backward_can_reuse_the_transposed_weights(K):
         g.backward(accumulate=8)
 
 
+@pytest.mark.parametrize("name,override", [("tiny", {"seq": 256}), ("small", {"batch": 2}), ("1b", {"batch": 1, "seq": 1024})])
+def test_recomputing_configurations_match_the_oracle_and_keep_less(K, name, override):
+    """recompute = norms | swiglu: h1, h2 and a are not kept in `saved`; the backward rebuilds them.  Same
+    bar against the oracle; outputs and every gradient but the down projection's equal the keeping
+    configuration's bit for bit (its operand a is rebuilt from the stored g and u when the fused kernel ran)."""
+    cfg = si.CONFIGS[name].with_(**override)
+    rc = cfg.with_(recompute=3)
+    inp = si.make_layer_inputs(cfg, seed=4)
+    f, r = _oracle(cfg, inp)
+    a, b = GpuLayer(K, cfg, inp), GpuLayer(K, rc, inp)
+    T, D, F = cfg.tokens, cfg.d_model, cfg.d_ff
+    assert K.dlayer_saved_bytes(cfg) - K.dlayer_saved_bytes(rc) >= 2 * T * (2 * D + F)
+    a.forward(); a.backward()
+    b.forward(); b.backward()
+    torch.cuda.synchronize()
+    _check_layer(b, f, r, name + ":recompute")
+    for n_, p, q in [("y", a.y, b.y), ("dx", a.dx, b.dx)] + [(n, a.dw[n], b.dw[n]) for n in si.WEIGHT_NAMES if n != "w_down"]:
+        assert torch.equal(p.view(torch.int16), q.view(torch.int16)), f"{n_} differs between keeping and recomputing"
+
+
 def test_layer_is_causal_and_deterministic(K):
     cfg = si.CONFIGS["tiny"].with_(seq=256, batch=2)
     inp = si.make_layer_inputs(cfg, seed=1)
