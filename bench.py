@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/
 # shapes of the 8B-shaped layer), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain 1 GiB copy in the same
 # run (factors 2.0 and 1.0; profiles/layer_8b_hbm_traffic.txt).  Only valid for the GEMM source the
 # counters were taken on: reported as null when gemm.hip has changed since.
-GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "4f1eb6845b6f9eb626e56b1610efe3c19f59d651cce32017576058bacc1b9ad2",
+GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "7c531aa1417ffd8670bd126182a0d2cd828ff11f671541043a16cdbfe839a0f8",
                 "fetch_bytes": 1.496e+09, "write_bytes": 2.013e+08}
 
 
@@ -257,6 +257,8 @@ def main():
     ap.add_argument("--cpu-full", action="store_true",
                     help="also run the oracle once over the whole workload (about two minutes of host time at the 8B shape)")
     ap.add_argument("--no-components", action="store_true", help="skip the per-piece timing table")
+    ap.add_argument("--recompute", type=int, default=0,
+                    help="dlayer_cfg.recompute bits (1: rebuild h1, h2 in the backward; 2: rebuild the SwiGLU output); 0 is the timed default")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size dispatch that HBM byte "
                          "counters of a profiler run are scaled by)")
@@ -277,7 +279,7 @@ def main():
         return bench_stack(args, torch, K, si, dev_bf16)
     if args.config == "optimizer":
         return bench_optimizer(args, torch, K, si)
-    cfg = si.CONFIGS[args.config]
+    cfg = si.CONFIGS[args.config].with_(recompute=args.recompute)
     inp = si.make_layer_inputs(cfg, seed=0)
     x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])
     w = {n: dev_bf16(inp[n]) for n in si.WEIGHT_NAMES}
@@ -374,7 +376,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": _describe(cfg), "name": args.config, "tokens_per_step": cfg.tokens,
-                   "flops_per_step": flops},
+                   "flops_per_step": flops, "recompute": cfg.recompute, "saved_bytes": K.dlayer_saved_bytes(cfg)},
         "tokens_per_s": cfg.tokens / (ms * 1e-3), "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "peak_tflops": PEAK_BF16_TFLOPS, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
         "ms_per_step_median": step_median_ms, "ms_per_step_min": step_min_ms,
