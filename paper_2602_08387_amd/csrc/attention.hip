@@ -95,6 +95,27 @@ __device__ __forceinline__ bf16x8 pack_slots(const f32x16& a, int first) {
   return v;
 }
 
+
+// Value exchange between lane l and lane l ^ 32 without the LDS round trip of a bpermute: after the swap
+// `a` holds the low half's values in both halves and `b` the high half's.
+__device__ __forceinline__ float max_across_halves(float x) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return __builtin_fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_across_halves(float x) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return a + b;
+}
+// max of three as one instruction, without the canonicalising self-maximum the compiler puts in front of
+// fmaxf operands (scores are finite or -inf here, never NaN)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+
 // Causal mask for a score tile held in the "lane owns one query (or key) column" accumulator
 // layout: register r of 32-row block i holds row i*32 + 8*(r/4) + 4*(lane/32) + r%4.  `lim` is the
 // largest row offset this lane may keep (computed by the caller with the 4*(lane/32) folded in);
@@ -203,7 +224,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[i][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+    mx = max_across_halves(mx) * scale_log2;
     if (__builtin_amdgcn_ballot_w64(mx > m + 8.0f) != 0) {
       const float m_new = fmaxf(m, mx);
       const float alpha = fast_exp2(m - m_new);
@@ -235,7 +256,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
     __syncthreads();
     stage ^= 1;
   }
-  lsum += __shfl_xor(lsum, 32, 64);
+  lsum = sum_across_halves(lsum);
   const float inv = 1.0f / lsum;
   bf16_t* op = o + ((int64_t)b * S + qw + lq) * ldq + (int64_t)h * DH + half * 4;
 #pragma unroll
@@ -251,7 +272,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
 }
 
 // ------------------------------------------------------------------------------------------
-// delta[b, h, q] = sum_d dO[q, h, d] * O[q, h, d], and lse2 = lse * log2(e) (the exponent reference
+// delta[b, h, q] = -sum_d dO[q, h, d] * O[q, h, d] (negated: the dQ and dK kernels start their dP
+// accumulators from it, so dP - rowsum(dO * O) needs no subtraction), and lse2 = lse * log2(e) (the exponent reference
 // in the units the backward kernels' exp2 works in), both [B, Hq, S] fp32.
 // ------------------------------------------------------------------------------------------
 template <int DH>
@@ -275,7 +297,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restric
     const int64_t tok = row / Hq;
     const int h = (int)(row % Hq);
     const int64_t b = tok / S, qi = tok % S;
-    delta[(b * Hq + h) * S + qi] = acc;
+    delta[(b * Hq + h) * S + qi] = -acc;   // stored negated: the backward products start their dP sums from it
     lse2[(b * Hq + h) * S + qi] = lse[(b * Hq + h) * S + qi] * kLog2e;
   }
 }
@@ -352,7 +374,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     }
   }
   const int64_t stat = ((int64_t)b * Hq + h) * S + qw + lq;
-  const float lse2 = lse[stat] * kLog2e, dl = delta[stat];
+  const float lse2 = lse[stat] * kLog2e;
+  // dP - delta comes out of the product itself: the dP accumulator starts from -delta (this lane's query)
+  f32x16 neg_delta;
+  {
+    const float nd = delta[stat];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) neg_delta[e] = nd;
+  }
   f32x16 acc[DH / 32];
 #pragma unroll
   for (int t = 0; t < DH / 32; ++t)
@@ -380,9 +409,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     // two 32-key halves per tile: keeps the live score registers at 32 so two waves fit per SIMD
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      f32x16 s[1], dp;
+      f32x16 s[1], dp = neg_delta;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { s[0][e] = 0.f; dp[e] = 0.f; }
+      for (int e = 0; e < 16; ++e) s[0][e] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < DH / 16; ++kk) {
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tk, i * 32, kk, lane), qf[kk], s[0], 0, 0, 0);
@@ -393,7 +422,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const float pv = fast_exp2(__builtin_fmaf(s[0][r], scale_log2, -lse2));
-        s[0][r] = pv * (dp[r] - dl);  // dS^T
+        s[0][r] = pv * dp[r];  // dS^T = P^T (dP^T - delta)
       }
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
@@ -506,6 +535,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
       f32x16 s, dp;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+      if constexpr (!WANT_DV) {
+        // dP - delta comes out of the product itself: the dP accumulator starts from -delta of its query rows
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 64 + qs * 32 + g * 8 + half * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dp[g * 4 + e] = d4[e];
+        }
+      }
 #pragma unroll
       for (int kk = 0; kk < DH / 16; ++kk) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tq, qs * 32, kk, lane), kf[kk], s, 0, 0, 0);
@@ -516,13 +554,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
       for (int g = 0; g < 4; ++g) {
         const int ql = qs * 32 + g * 8 + half * 4;
         const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + ql);
-        f32x4 d4 = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (!WANT_DV) d4 = *reinterpret_cast<const f32x4*>(stat + 64 + ql);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = g * 4 + e;
           const float pv = fast_exp2(__builtin_fmaf(s[r], scale_log2, -l4[e]));
-          if constexpr (WANT_DV) s[r] = pv; else s[r] = pv * (dp[r] - d4[e]);   // P or dS
+          if constexpr (WANT_DV) s[r] = pv; else s[r] = pv * dp[r];   // P or dS = P (dP - delta)
         }
       }
       if (diag) {
@@ -584,7 +620,7 @@ int launch_attention_fwd(const void* q, const void* k, const void* v, int64_t B,
 }
 
 size_t attention_bwd_workspace(int64_t B, int64_t S, int64_t Hq, int64_t, int64_t) {
-  return 2 * (size_t)B * Hq * S * sizeof(float);   // delta and lse * log2(e)
+  return 2 * (size_t)B * Hq * S * sizeof(float);   // -rowsum(dO * O) and lse * log2(e)
 }
 
 template <int DH>
