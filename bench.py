@@ -246,6 +246,36 @@ def bench_optimizer(args, torch, K, si):
                      "frac": nbytes / (ms * 1e-3) / 1e9 / 8000.0, "traffic": None}}))
 
 
+PROBES = (
+    # family, variant, label; one block = 16 MFMAs 32x32x16 (family 0) or 8 MFMAs 16x16x32 (family 1)
+    (0, 0, "32x32x16 MFMAs alone"),
+    (0, 1, "softmax-like VALU work alone (16 exp + 64 fma per block)"),
+    (0, 2, "both, evenly interleaved (MFMA, 1 exp, 4 fma) x 16"),
+    (0, 3, "both, two regions: (MFMA, 1 fma) x 8 then (MFMA, 2 exp, 7 fma) x 8"),
+    (1, 0, "16x16x32 MFMAs, operands in registers"),
+    (1, 1, "  with 2 ds_read_b128 per 8 MFMAs (128x128 wave tile)"),
+    (1, 2, "  with 3 ds_read_b128 per 8 MFMAs (128x64 wave tile)"),
+    (1, 3, "  with 3 pairs of ds_read_b64_tr_b16 per 8 MFMAs (128x64, transposed operands)"),
+)
+
+
+def run_probes(K):
+    """Synthetic issue-rate measurements (C-ABI issue_rate_probe); flop rates count the MFMAs only."""
+    rows = []
+    for fam, var, label in PROBES:
+        for wps in (1, 2):
+            cyc, ms, ghz, _ = K.issue_rate_probe(fam, var, wps)
+            mfmas = 0 if (fam, var) == (0, 1) else 256 * 4 * wps * 2000 * (16 if fam == 0 else 8 * 2)
+            flop = mfmas * (32768.0 if fam == 0 else 16384.0)
+            rows.append({"probe": label, "waves_per_simd": wps, "cycles_per_block_per_simd": round(cyc, 1),
+                         "ms": round(ms, 3), "shader_ghz": round(ghz, 2), "mfma_tflops": round(flop / ms / 1e9, 0)})
+    for var, label in ((0, "MFMA waves alone"), (1, "VALU waves alone"), (2, "MFMA waves and VALU waves side by side")):
+        cyc, ms, ghz, other = K.issue_rate_probe(2, var, 2)
+        rows.append({"probe": "neighbouring waves: " + label, "cycles_per_mfma": round(cyc, 1), "cycles_per_fma": round(other, 2),
+                     "ms": round(ms, 3), "shader_ghz": round(ghz, 2)})
+    print(json.dumps({"probes": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -262,6 +292,9 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size dispatch that HBM byte "
                          "counters of a profiler run are scaled by)")
+    ap.add_argument("--probes", action="store_true",
+                    help="instead of the step: run the library's synthetic issue-rate probes (matrix pipe next to "
+                         "VALU work, LDS operand feed, neighbouring waves) and print their table as one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU decoder-layer step; this library has no multi-GPU path "
@@ -275,6 +308,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.probes:
+        return run_probes(K)
     if args.config == "stack":
         return bench_stack(args, torch, K, si, dev_bf16)
     if args.config == "optimizer":

@@ -310,6 +310,24 @@ int adamw_step(int32_t n, void* const* params, const void* const* grads, float* 
                float beta2, float eps, float weight_decay, float max_grad_norm, const float* sq_norm,
                void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Measurement aid, not a step of the path: synthetic kernels that time the matrix pipe next to a set
+ * amount of other work on this GPU (one workgroup per compute unit, fixed trip counts, no inputs).
+ * They back the design notes on what bounds the GEMM and attention kernels; bench.py --probes
+ * prints the table.
+ *   family 0  32x32x16 MFMAs and softmax-like VALU work, one block = 16 MFMAs + 16 exp + 64 fma:
+ *             variant 0 MFMAs alone, 1 VALU alone, 2 evenly interleaved, 3 in two regions
+ *             (8 MFMAs with 1 fma each, then 8 with 2 exp + 7 fma each)
+ *   family 1  16x16x32 MFMAs fed from LDS, one block = 8 MFMAs: variant 0 no reads, 1 two and 2 three
+ *             16-byte fragment reads per block, 3 three pairs of transposing 8-byte reads
+ *   family 2  four waves issue MFMAs only, their four SIMD partners v_fma_f32 only (waves_per_simd is
+ *             ignored): variant 0 the MFMA waves alone, 1 the VALU waves alone, 2 both
+ * waves_per_simd: 1 or 2.  result (host, 4 doubles): shader-clock cycles per block per SIMD (family 2:
+ * per MFMA of an MFMA wave), milliseconds of the launch, shader clock in GHz during it, and for family
+ * 2 the cycles per fma of a VALU wave (else 0).  Allocates and frees a few KB of device memory and
+ * synchronises with the stream.                                                                   */
+int issue_rate_probe(int family, int variant, int waves_per_simd, double* result, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ _BINDING_NAMES = (
     "linear_swiglu_backward_workspace_bytes", "linear_backward", "linear_backward_workspace_bytes", "linear_wgrad_group",
     "rope_apply", "attention_forward", "attention_backward", "attention_backward_workspace_bytes",
     "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward_workspace_bytes", "embed_backward",
-    "grad_sq_norm_workspace_bytes", "grad_sq_norm", "adamw_step",
+    "grad_sq_norm_workspace_bytes", "grad_sq_norm", "adamw_step", "issue_rate_probe",
     "EXPORTED_SYMBOLS", "WEIGHT_FIELDS",
 )
 

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = (
     "linear_swiglu_backward", "linear_backward_workspace_bytes", "linear_backward", "linear_wgrad_group", "rope_apply",
     "attention_forward", "attention_backward_workspace_bytes", "attention_backward",
     "swiglu_forward", "swiglu_backward", "embed_forward", "embed_backward_workspace_bytes", "embed_backward",
-    "grad_sq_norm_workspace_bytes", "grad_sq_norm", "adamw_step",
+    "grad_sq_norm_workspace_bytes", "grad_sq_norm", "adamw_step", "issue_rate_probe",
 )
 
 
@@ -96,6 +96,7 @@ def _load():
         "grad_sq_norm_workspace_bytes": (sz, [i32, vp]),
         "grad_sq_norm": (C.c_int, [i32, vp, vp, vp, C.c_int, vp, vp]),
         "adamw_step": (C.c_int, [i32, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, f32, vp, vp]),
+        "issue_rate_probe": (C.c_int, [C.c_int, C.c_int, C.c_int, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(l, name)
@@ -307,3 +308,10 @@ def adamw_step(params, grads, exp_avg, exp_avg_sq, step, lr, beta1, beta2, eps, 
     _check(lib.adamw_step(n, _ptr_list(params), _ptr_list(grads), _ptr_list(exp_avg), _ptr_list(exp_avg_sq),
                           _numel_list(params), int(step), lr, beta1, beta2, eps, weight_decay, max_grad_norm,
                           _p(sq_norm), _stream(stream)), "adamw_step")
+
+
+def issue_rate_probe(family, variant, waves_per_simd=2, stream=None):
+    """(cycles per block per SIMD, milliseconds, shader clock in GHz, second role's cycles per op)"""
+    out = (C.c_double * 4)()
+    _check(lib.issue_rate_probe(family, variant, waves_per_simd, out, _stream(stream)), "issue_rate_probe")
+    return tuple(out)

@@ -9,7 +9,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdlayer.so")
-SOURCES = ("api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "ce.hip", "optimizer.hip")
+SOURCES = ("api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "ce.hip", "optimizer.hip", "probes.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -127,4 +127,8 @@ int launch_adamw(int n, void* const* p, const void* const* g, float* const* m, f
                  int64_t step, float lr, float beta1, float beta2, float eps, float weight_decay, float max_norm,
                  const float* sq_norm, hipStream_t st);
 
+// probes.hip: synthetic issue-rate measurements (see the file's header for families and variants);
+// result[4] = cycles per block per SIMD, milliseconds, shader clock in GHz, second role's cycles per op
+int launch_probe(int family, int variant, int waves_per_simd, double* result, hipStream_t st);
+
 }  // namespace dl

@@ -509,3 +509,20 @@ def test_bad_arguments_are_rejected_before_any_launch(K):
     assert (y == 3.0).all()
     bad = si.CONFIGS["tiny"].with_(head_dim=48)
     assert K.dlayer_saved_bytes(bad) == 0 and K.dlayer_workspace_bytes(bad) == 0
+
+
+# ------------------------------------------------------------------ measurement aid
+def test_issue_rate_probe_reports_the_matrix_pipe_rate(K):
+    """A 32x32x16 bf16 MFMA occupies a SIMD's matrix pipe for 32 cycles (2 * 32 * 32 * 16 flop at 1024 flop
+    per cycle and SIMD, the rate behind the 2.5 PFLOP/s figure): the probe that issues nothing else must
+    report 16 * 32 cycles per block, at a shader clock a GPU can have, and reject what it does not know."""
+    for waves in (1, 2):
+        cycles, ms, ghz, _ = K.issue_rate_probe(0, 0, waves)
+        assert 500.0 < cycles < 540.0, (waves, cycles)
+        assert ms > 0.0 and 0.5 < ghz < 3.0, (ms, ghz)
+    both = K.issue_rate_probe(0, 2, 2)[0]
+    assert 512.0 <= both < 1024.0      # VALU work next to the MFMAs costs something, less than running it after them
+    with pytest.raises(K.DLayerError):
+        K.issue_rate_probe(3, 0, 2)
+    with pytest.raises(K.DLayerError):
+        K.issue_rate_probe(0, 0, 3)
