@@ -1,4 +1,5 @@
-"""Builds libdlayer.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
+"""Builds libdlayer.so (HIP kernels + C ABI) for gfx950 with hipcc and libtokpipe.so (the data
+pipeline's tokenization stage, host code) with g++, in-tree."""
 from __future__ import annotations
 
 import os
@@ -9,6 +10,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdlayer.so")
+TOKPIPE_LIB_PATH = os.path.join(PKG_DIR, "libtokpipe.so")
 SOURCES = ("api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "ce.hip", "optimizer.hip", "probes.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -35,7 +37,20 @@ def build(verbose: bool = False, jobs: int = 6) -> str:
     out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if out.returncode != 0:
         raise RuntimeError("link failed:\n" + out.stdout)
+    build_tokpipe(verbose)
     return LIB_PATH
+
+
+def build_tokpipe(verbose: bool = False) -> str:
+    cxx = shutil.which("g++") or "g++"
+    cmd = [cxx, "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread", "-Wall", "-Wextra",
+           os.path.join(CSRC, "tokpipe.cpp"), "-o", TOKPIPE_LIB_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if out.returncode != 0:
+        raise RuntimeError("g++ failed on tokpipe.cpp:\n" + out.stdout)
+    return TOKPIPE_LIB_PATH
 
 
 def _drain(procs, verbose):
