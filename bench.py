@@ -246,6 +246,57 @@ def bench_optimizer(args, torch, K, si):
                      "frac": nbytes / (ms * 1e-3) / 1e9 / 8000.0, "traffic": None}}))
 
 
+def bench_tokenize(args):
+    """The data pipeline's tokenization stage (host only, no GPU): indexation + producer-consumer
+    tokenization of a synthetic JSONL corpus into a token file.  A step is one pass over the corpus."""
+    import tempfile
+    from synth import text as st
+    from paper_2602_08387_amd import tokpipe as tp
+    workers = args.tok_workers or min(16, os.cpu_count() or 1)
+    merges = st.train_merges(0, 2000, 4000)
+    eod = 256 + len(merges)
+    with tempfile.TemporaryDirectory(prefix="tokbench_") as tmp:
+        src, idx, out = (os.path.join(tmp, n) for n in ("corpus.jsonl", "corpus.idx", "corpus.tok"))
+        with open(src, "wb") as f:           # distinct documents, made in parts to bound memory
+            part, size = 0, 0
+            while size < args.tok_megabytes * 1e6:
+                chunk = st.make_jsonl(1000 + part, 1500, n_words=20000)
+                f.write(chunk if chunk.endswith(b"\n") else chunk + b"\n")
+                size += len(chunk) + 1
+                part += 1
+        t_index = []
+        runs = []
+        for it in range(args.warmup + args.steps):
+            t0 = time.perf_counter()
+            n_docs = tp.index_jsonl(src, idx, workers)
+            t1 = time.perf_counter()
+            stats = tp.tokenize(src, idx, out, merges, "text", eod, workers, args.tok_batch, 4 * workers)
+            t2 = time.perf_counter()
+            if it >= args.warmup:
+                t_index.append(t1 - t0)
+                runs.append((t2 - t0, stats.n_tokens, stats.bytes_read, stats.cache_hits, stats.cache_misses))
+        sec = sum(r[0] for r in runs) / len(runs)
+        tokens, nbytes = runs[-1][1], runs[-1][2]
+        rec = {"metric": "tokenization throughput, indexation included", "value": tokens / sec, "unit": "tokens/s", "n_gpus": 1,
+               "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
+               "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+               "config": {"workload": f"JSONL -> token file: {n_docs} synthetic documents, {nbytes / 1e6:.0f} MB, byte-level BPE with "
+                                      f"{len(merges)} merges; 1 reader, {workers} tokenizer workers, 1 writer, batches of {args.tok_batch} documents",
+                          "name": "tokenize", "tokens": int(tokens), "documents": int(n_docs), "index_ms": 1e3 * sum(t_index) / len(t_index),
+                          "megabytes_per_s": nbytes / sec / 1e6, "piece_cache_hit_rate": runs[-1][3] / max(1, runs[-1][3] + runs[-1][4])},
+               "roofline": None, "note": "host-only workload: no GPU kernel runs, so no GPU roofline applies"}
+        if not args.no_cpu_baseline:
+            from oracle import tokenize as ot
+            sample = open(src, "rb").read(int(args.tok_oracle_megabytes * 1e6))
+            sample = sample[:sample.rfind(b"\n") + 1]
+            t0 = time.perf_counter()
+            docs = ot.tokenize_jsonl(sample, merges, "text", eod)
+            dt = time.perf_counter() - t0
+            rec["cpu_baseline"] = {"value": sum(map(len, docs)) / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle", "seconds": dt,
+                                   "sample": f"the first {len(sample) / 1e6:.1f} MB of the same corpus ({len(docs)} documents), sequential Python"}
+    print(json.dumps(rec))
+
+
 PROBES = (
     # family, variant, label; one block = 16 MFMAs 32x32x16 (family 0) or 8 MFMAs 16x16x32 (family 1)
     (0, 0, "32x32x16 MFMAs alone"),
@@ -281,7 +332,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b", "70b_width", "stack", "optimizer"])
+    ap.add_argument("--config", default="8b", choices=["tiny", "small", "1b", "8b", "70b_width", "stack", "optimizer", "tokenize"])
+    ap.add_argument("--tok-megabytes", type=float, default=120.0, help="--config tokenize: size of the synthetic corpus")
+    ap.add_argument("--tok-workers", type=int, default=0, help="--config tokenize: tokenizer threads (default: host cores, at most 16)")
+    ap.add_argument("--tok-batch", type=int, default=64, help="--config tokenize: documents per queue entry")
+    ap.add_argument("--tok-oracle-megabytes", type=float, default=6.0, help="--config tokenize: corpus prefix the oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=4096)
     ap.add_argument("--cpu-full", action="store_true",
@@ -300,6 +355,9 @@ def main():
         print("bench.py measures the single-GPU decoder-layer step; this library has no multi-GPU path "
               "(no collectives, no sharding): run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.config == "tokenize":
+        return bench_tokenize(args)
 
     import torch
     import paper_2602_08387_amd as K   # raises if the HIP library is not built: no fallback
