@@ -30,7 +30,6 @@
 #include <mutex>
 #include <string>
 #include <thread>
-#include <unordered_map>
 #include <vector>
 
 namespace {
@@ -284,16 +283,85 @@ struct MergeTable {
   }
 };
 
+// Cache of pieces already merged: open addressing over one arena that holds, per entry, the piece's
+// bytes followed by its tokens.  Natural text repeats its words, so most pieces are found here and cost
+// one hash and one comparison instead of the merge loop.
+struct PieceCache {
+  struct Slot { uint64_t hash; uint32_t at; uint16_t len, ntok; };   // at: offset of the entry in `arena`
+  std::vector<Slot> slots;
+  std::vector<unsigned char> arena;
+  uint64_t mask = 0;
+  size_t used = 0;
+  static constexpr size_t kArenaLimit = 64u << 20;   // per worker; beyond it the cache starts over
+  PieceCache() { reset(); }
+  void reset() {
+    slots.assign(1u << 16, Slot{0, UINT32_MAX, 0, 0});
+    mask = slots.size() - 1;
+    used = 0;
+    arena.clear();
+    arena.reserve(1u << 20);
+  }
+  static uint64_t hash(const unsigned char* p, int n) {
+    uint64_t h = 0x9E3779B97F4A7C15ull ^ (uint64_t)n;
+    int i = 0;
+    for (; i + 8 <= n; i += 8) {
+      uint64_t w;
+      memcpy(&w, p + i, 8);
+      h = (h ^ w) * 0xFF51AFD7ED558CCDull;
+      h ^= h >> 32;
+    }
+    uint64_t w = 0;
+    if (i < n) memcpy(&w, p + i, (size_t)(n - i));
+    h = (h ^ w) * 0xC4CEB9FE1A85EC53ull;
+    return h ^ (h >> 29);
+  }
+  // tokens of the piece or nullptr; *slot_out is where insert() must put it
+  const uint32_t* find(const unsigned char* p, int n, uint64_t h, int* ntok, size_t* slot_out) const {
+    size_t i = h & mask;
+    for (;; i = (i + 1) & mask) {
+      const Slot& s = slots[i];
+      if (s.at == UINT32_MAX) { *slot_out = i; return nullptr; }
+      if (s.hash == h && s.len == n && memcmp(arena.data() + s.at, p, (size_t)n) == 0) {
+        *ntok = s.ntok;
+        return reinterpret_cast<const uint32_t*>(arena.data() + s.at + ((n + 3) & ~3));
+      }
+    }
+  }
+  void insert(size_t slot, const unsigned char* p, int n, uint64_t h, const uint32_t* tok, int ntok) {
+    const size_t need = (size_t)((n + 3) & ~3) + (size_t)ntok * 4;
+    if (arena.size() + need > kArenaLimit || (used + 1) * 2 > slots.size()) {
+      if (arena.size() + need > kArenaLimit) { reset(); slot = h & mask; }
+      else { grow(); int d; if (find(p, n, h, &d, &slot)) return; }
+    }
+    const size_t at = (arena.size() + 3) & ~(size_t)3;
+    arena.resize(at + need);
+    memcpy(arena.data() + at, p, (size_t)n);
+    memcpy(arena.data() + at + ((n + 3) & ~3), tok, (size_t)ntok * 4);
+    slots[slot] = Slot{h, (uint32_t)at, (uint16_t)n, (uint16_t)ntok};
+    ++used;
+  }
+  void grow() {
+    std::vector<Slot> old;
+    old.swap(slots);
+    slots.assign(old.size() * 2, Slot{0, UINT32_MAX, 0, 0});
+    mask = slots.size() - 1;
+    for (const Slot& s : old)
+      if (s.at != UINT32_MAX) {
+        size_t i = s.hash & mask;
+        while (slots[i].at != UINT32_MAX) i = (i + 1) & mask;
+        slots[i] = s;
+      }
+  }
+};
+
 struct Encoder {
   const MergeTable& table;
-  std::unordered_map<std::string, std::vector<uint32_t>> cache;
-  size_t cache_bytes = 0;
+  PieceCache cache;
   uint64_t hits = 0, misses = 0;
-  static constexpr size_t kCacheLimit = 64u << 20;   // per worker; the cache is dropped and rebuilt beyond
   explicit Encoder(const MergeTable& t) : table(t) {}
 
-  void merge_piece(const unsigned char* p, int n, std::vector<uint32_t>& out) {
-    uint32_t sym[kMaxPiece];
+  // symbols of the piece after all merges, into sym[]; returns their number
+  int merge_piece(const unsigned char* p, int n, uint32_t* sym) {
     for (int i = 0; i < n; ++i) sym[i] = p[i];
     while (n > 1) {
       uint32_t best = UINT32_MAX;
@@ -307,24 +375,24 @@ struct Encoder {
       memmove(sym + at + 1, sym + at + 2, (size_t)(n - at - 2) * sizeof(uint32_t));
       --n;
     }
-    out.insert(out.end(), sym, sym + n);
+    return n;
   }
 
   void piece(const unsigned char* p, int n, std::vector<uint32_t>& out) {
     if (n == 1) { out.push_back(p[0]); return; }
-    std::string k((const char*)p, (size_t)n);
-    auto it = cache.find(k);
-    if (it != cache.end()) {
+    const uint64_t h = PieceCache::hash(p, n);
+    int ntok = 0;
+    size_t slot = 0;
+    if (const uint32_t* tok = cache.find(p, n, h, &ntok, &slot)) {
       ++hits;
-      out.insert(out.end(), it->second.begin(), it->second.end());
+      out.insert(out.end(), tok, tok + ntok);
       return;
     }
     ++misses;
-    const size_t before = out.size();
-    merge_piece(p, n, out);
-    if (cache_bytes > kCacheLimit) { cache.clear(); cache_bytes = 0; }
-    cache_bytes += (size_t)n + (out.size() - before) * 4 + 64;
-    cache.emplace(std::move(k), std::vector<uint32_t>(out.begin() + (long)before, out.end()));
+    uint32_t sym[kMaxPiece];
+    ntok = merge_piece(p, n, sym);
+    out.insert(out.end(), sym, sym + ntok);
+    cache.insert(slot, p, n, h, sym, ntok);
   }
 
   void encode(const unsigned char* t, size_t n, std::vector<uint32_t>& out) {
