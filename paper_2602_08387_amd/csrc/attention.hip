@@ -451,12 +451,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// dK or dV (template flag).  Workgroup = 4 waves = 128 keys of one (batch, kv head); wave = 32 keys.
-// Streams the Q and dO tiles (64 query rows) of every query head of the group, from the last query
-// tile back to the diagonal.  One kernel holding both accumulators needs 192 registers of state and runs one wave
-// per SIMD at 30 % MFMA utilisation (measured); computing dV (S, dV^T products) and dK (S, dP, dK^T
-// products) in two launches costs one more S product but each fits two waves per SIMD, so one wave's
-// exp/dS arithmetic runs under the other's MFMAs.
+// dK or dV (template flag), the two-launch form kept for head dim 32 (whose 32-row tiles are too small to
+// split over four loading waves in attn_bwd_dkdv_kernel).  Workgroup = 4 waves = 128 keys of one (batch,
+// kv head); wave = 32 keys.  Streams the Q and dO tiles (64 query rows) of every query head of the group,
+// from the last query tile back to the diagonal: dV takes the S and dV^T products, dK the S, dP and dK^T
+// products.
 // ------------------------------------------------------------------------------------------
 template <int DH, bool WANT_DV>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
@@ -599,6 +598,158 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// dK and dV in one pass (head dims 64 and 128).  Workgroup = 4 waves = 128 keys of one (batch, kv head),
+// wave = 32 keys; it streams 32-row Q / dO tiles of every query head of the group from the last query
+// tile back to the diagonal.  Per tile: S = Q K^T and dP = dO V^T - delta once, P = exp2(..), dS = P dP,
+// then dV^T += dO^T P and dK^T += Q^T dS: 4 products where the two separate kernels run 5, one
+// exponential pass instead of two, and every Q / dO tile crosses L2 -> LDS once instead of twice.
+// To hold both accumulators at two waves per SIMD the wave's V fragments live in LDS (the 128-key V tile
+// stays resident), only its K fragments in registers, and the query tile is 32 rows.
+// ------------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+    const bf16_t* __restrict__ d_o, const float* __restrict__ lse2, const float* __restrict__ delta,
+    bf16_t* __restrict__ dk_out, bf16_t* __restrict__ dv_out, int B, int S, int Hq, int Hkv, float scale,
+    const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, int rope_layout) {
+  using VTile = RowTile<128, DH, 4>;
+  using Tile = RowTile<32, DH, 1>;          // addressing of a 32-row tile; loaded by issue32 below
+  constexpr int TB = 32 * DH * 2;           // one Q or dO tile
+  constexpr int STAGE = 2 * TB + 512;       // Q tile, dO tile, lse2[32] (+ pad), delta[32] (+ pad)
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  char* tv = smem + 2 * STAGE;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int kt, pair;   // low key tiles have the most query tiles: first
+  split_block_id((int)blockIdx.x, B * Hkv, kt, pair);
+  const int G = Hq / Hkv, b = pair / Hkv, hk = pair % Hkv;
+  const int kv0 = kt * 128, kvw = kv0 + wave * 32;
+  const int lk = lane & 31, half = lane >> 5;
+  const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
+  const float scale_log2 = scale * kLog2e;
+
+  bf16x8 kf[DH / 16];
+  {
+    const int64_t off = ((int64_t)b * S + kvw + lk) * ldk + (int64_t)hk * DH + half * 8;
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk) kf[kk] = *reinterpret_cast<const bf16x8*>(k + off + kk * 16);
+  }
+  f32x16 acc_k[DH / 32], acc_v[DH / 32];
+#pragma unroll
+  for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { acc_k[t][e] = 0.f; acc_v[t][e] = 0.f; }
+
+  const int nq = (S - kv0) / 32, niter = G * nq;
+  const uint32_t q_bytes = (uint32_t)((((int64_t)S - 1) * ldq + DH) * 2);
+  // 32 rows x DH*2 bytes = 32*DH*2/1024 wave-wide loads per tile, dealt to the four waves
+  constexpr int RPI = 1024 / (DH * 2), NI = 32 / RPI, IPW = NI / 4;
+  static_assert(NI % 4 == 0 && IPW >= 1, "a 32-row tile must split over four waves");
+  auto issue32 = [&](const bf16_t* base, uint32_t bytes, char* dst) {
+    const __amdgpu_buffer_rsrc_t rs = attn_rsrc(base, bytes);
+    const int r = lane / Tile::LPR, pc = lane % Tile::LPR;
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+      const int j = wave * IPW + i, row = j * RPI + r;
+      const int c = pc ^ Tile::swz(row);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(dst + j * 1024), 16, (uint32_t)(r * ldq * 2 + (c << 4)),
+                                               (uint32_t)((int64_t)j * RPI * ldq * 2), 0, 0);
+    }
+  };
+  int ld_g = 0, ld_qt = S / 32 - 1, cur_g = 0, cur_qt = S / 32 - 1;
+  auto issue_tile = [&](int stage) {
+    const int h = hk * G + ld_g, qrow = ld_qt * 32;
+    if (++ld_g == G) { ld_g = 0; --ld_qt; }
+    const int64_t base = ((int64_t)b * S) * ldq + (int64_t)h * DH;
+    const uint32_t skip = (uint32_t)((int64_t)qrow * ldq * 2);
+    char* st = smem + stage * STAGE;
+    issue32(q + base + (int64_t)qrow * ldq, q_bytes - skip, st);
+    issue32(d_o + base + (int64_t)qrow * ldq, q_bytes - skip, st + TB);
+    // 32 lse2 and 32 -delta values of the tile, 4 bytes per lane, lanes 32..63 out of range (they store zeros into the pad)
+    const int64_t sidx = ((int64_t)b * Hq + h) * S + qrow;
+    if (wave == 0)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(attn_rsrc(lse2 + sidx, 128), (LDS_PTR(void))(st + 2 * TB), 4, (uint32_t)lane * 4, 0, 0, 0);
+    if (wave == 1)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(attn_rsrc(delta + sidx, 128), (LDS_PTR(void))(st + 2 * TB + 256), 4, (uint32_t)lane * 4, 0, 0, 0);
+  };
+  {
+    // the workgroup's 128 rows of V stay in LDS; wave w loads (and later reads) rows 32 w .. 32 w + 31
+    const uint32_t kv_bytes = (uint32_t)((((int64_t)S - 1) * ldk + DH) * 2);
+    const bf16_t* vb = v + ((int64_t)b * S + kv0) * ldk + (int64_t)hk * DH;
+    VTile::issue(attn_rsrc(vb, kv_bytes - (uint32_t)((int64_t)kv0 * ldk * 2)), tv, wave, lane, ldk);
+  }
+  issue_tile(0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  int stage = 0;
+  for (int it = 0; it < niter; ++it) {
+    if (it + 1 < niter) issue_tile(stage ^ 1);
+    const int qrow = cur_qt * 32;
+    if (++cur_g == G) { cur_g = 0; --cur_qt; }
+    const char* tq = smem + stage * STAGE;
+    const char* tdo = tq + TB;
+    const float* stat = reinterpret_cast<const float*>(tq + 2 * TB);
+    // S[q][kv] and dP[q][kv] - delta[q] for the 32 queries: lane owns key kvw + lk, queries along registers
+    f32x16 s, dp;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 64 + g * 8 + half * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { s[g * 4 + e] = 0.f; dp[g * 4 + e] = d4[e]; }
+    }
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tq, 0, kk, lane), kf[kk], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(tdo, 0, kk, lane), VTile::frag_rows(tv, wave * 32, kk, lane), dp, 0, 0, 0);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + g * 8 + half * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = g * 4 + e;
+        const float pv = fast_exp2(__builtin_fmaf(s[r], scale_log2, -l4[e]));
+        s[r] = pv;            // P
+        dp[r] = pv * dp[r];   // dS = P (dP - delta)
+      }
+    }
+    if (qrow < kvw + 31) {
+      // queries before the key are masked: P = dS = 0 for query rows below kvw + lk - qrow
+      asm volatile("" ::: "memory");
+      const int first_ok = kvw + lk - qrow - (half << 2);
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (((r >> 2) << 3) + (r & 3) < first_ok) { s[r] = 0.f; dp[r] = 0.f; }
+    }
+    // dV^T[d][kv] += dO^T[d][q] P[q][kv]   and   dK^T[d][kv] += Q^T[d][q] dS[q][kv]
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const bf16x8 pf = pack_slots(s, ks * 8), df = pack_slots(dp, ks * 8);
+#pragma unroll
+      for (int t2 = 0; t2 < DH / 32; ++t2) {
+        acc_v[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tdo, t2 * 32, ks * 16, lane), pf, acc_v[t2], 0, 0, 0);
+        acc_k[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tq, t2 * 32, ks * 16, lane), df, acc_k[t2], 0, 0, 0);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    stage ^= 1;
+  }
+  if (rope_cos) rope_unrotate<DH>(acc_k, rope_cos + (int64_t)(kvw + lk) * (DH / 2), rope_sin + (int64_t)(kvw + lk) * (DH / 2), rope_layout, half);
+  const int64_t off = ((int64_t)b * S + kvw + lk) * ldk + (int64_t)hk * DH + half * 4;
+#pragma unroll
+  for (int t2 = 0; t2 < DH / 32; ++t2)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 ok, ov;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { ok[e] = (bf16_t)(acc_k[t2][g * 4 + e] * scale); ov[e] = (bf16_t)acc_v[t2][g * 4 + e]; }
+      *reinterpret_cast<bf16x4*>(dk_out + off + t2 * 32 + g * 8) = ok;
+      *reinterpret_cast<bf16x4*>(dv_out + off + t2 * 32 + g * 8) = ov;
+    }
+}
+
+
+// ------------------------------------------------------------------------------------------
 template <int DH>
 static int fwd_dh(const void* q, const void* k, const void* v, int64_t B, int64_t S, int64_t Hq,
                   int64_t Hkv, void* o, float* lse, hipStream_t st) {
@@ -637,20 +788,31 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
   if (int rc = check_launch("attention_backward(delta)")) return rc;
   const float scale = (float)(1.0 / sqrt((double)DH));
   const size_t lds_dq = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
-  const size_t lds_kv = 2 * (2 * (size_t)RowTile<64, DH, 4>::BYTES + 512);
-  static std::atomic<unsigned long long> done_dq{0}, done_dv{0}, done_dk{0};
+  static std::atomic<unsigned long long> done_dq{0};
   if (int rc = reserve_lds(attn_bwd_dq_kernel<DH>, lds_dq, done_dq, "attention_backward")) return rc;
-  if (int rc = reserve_lds(attn_bwd_dkv_kernel<DH, true>, lds_kv, done_dv, "attention_backward")) return rc;
-  if (int rc = reserve_lds(attn_bwd_dkv_kernel<DH, false>, lds_kv, done_dk, "attention_backward")) return rc;
   const dim3 kv_grid((unsigned)(S / 128 * Hkv * B));
-  hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, true>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
-                     (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dv, (int)B, (int)S, (int)Hq,
-                     (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
-  if (int rc = check_launch("attention_backward(dv)")) return rc;
-  hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, false>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
-                     (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (int)B, (int)S, (int)Hq,
-                     (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
-  if (int rc = check_launch("attention_backward(dk)")) return rc;
+  if constexpr (DH >= 64) {
+    const size_t lds_m = 2 * (2 * (size_t)(32 * DH * 2) + 512) + (size_t)RowTile<128, DH, 4>::BYTES;
+    static std::atomic<unsigned long long> done_m{0};
+    if (int rc = reserve_lds(attn_bwd_dkdv_kernel<DH>, lds_m, done_m, "attention_backward")) return rc;
+    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<DH>, kv_grid, dim3(256), lds_m, st, (const bf16_t*)q, (const bf16_t*)k,
+                       (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (bf16_t*)dv,
+                       (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+    if (int rc = check_launch("attention_backward(dk, dv)")) return rc;
+  } else {
+    const size_t lds_kv = 2 * (2 * (size_t)RowTile<64, DH, 4>::BYTES + 512);
+    static std::atomic<unsigned long long> done_dv{0}, done_dk{0};
+    if (int rc = reserve_lds(attn_bwd_dkv_kernel<DH, true>, lds_kv, done_dv, "attention_backward")) return rc;
+    if (int rc = reserve_lds(attn_bwd_dkv_kernel<DH, false>, lds_kv, done_dk, "attention_backward")) return rc;
+    hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, true>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
+                       (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dv, (int)B, (int)S, (int)Hq,
+                       (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+    if (int rc = check_launch("attention_backward(dv)")) return rc;
+    hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, false>), kv_grid, dim3(256), lds_kv, st, (const bf16_t*)q, (const bf16_t*)k,
+                       (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (int)B, (int)S, (int)Hq,
+                       (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+    if (int rc = check_launch("attention_backward(dk)")) return rc;
+  }
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3((unsigned)(S / 128 * Hq * B)), dim3(256),
                      lds_dq, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)d_o, lse,
                      (const float*)delta, (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
