@@ -307,6 +307,10 @@ PROBES = (
     (1, 1, "  with 2 ds_read_b128 per 8 MFMAs (128x128 wave tile)"),
     (1, 2, "  with 3 ds_read_b128 per 8 MFMAs (128x64 wave tile)"),
     (1, 3, "  with 3 pairs of ds_read_b64_tr_b16 per 8 MFMAs (128x64, transposed operands)"),
+    # about a second of back-to-back launches each, pseudo-random operands: the rate at the clock the power limit allows
+    (3, 0, "sustained, random operands: 16x16x32 MFMAs, operands in registers"),
+    (3, 1, "sustained, random operands:   with 2 ds_read_b128 per 8 MFMAs"),
+    (3, 2, "sustained, random operands:   with 3 ds_read_b128 per 8 MFMAs"),
 )
 
 

@@ -680,7 +680,7 @@ int embed_backward(const void* dx0, const int64_t* ids, int64_t T, int64_t V, in
 
 int issue_rate_probe(int family, int variant, int waves_per_simd, double* result, void* stream) {
   REQUIRE(result != nullptr, "issue_rate_probe: result is null");
-  REQUIRE(family >= 0 && family <= 2 && variant >= 0 && variant <= 3, "issue_rate_probe: family 0..2, variant 0..3");
+  REQUIRE(family >= 0 && family <= 3 && variant >= 0 && variant <= 3, "issue_rate_probe: family 0..3, variant 0..3");
   TRY(check_device());
   return launch_probe(family, variant, waves_per_simd, result, (hipStream_t)stream);
 }

@@ -30,6 +30,13 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Logistic function from v_exp_f32 and v_rcp_f32 (about 1 ulp each; every use rounds the result to
+// bf16 afterwards).  Written as a division it compiles to the correctly rounded sequence of some ten
+// instructions per element, which the SwiGLU epilogues of the GEMMs (64 or 128 elements per lane and
+// tile, the matrix pipe idle meanwhile) pay for in full.  Every SwiGLU kernel uses this one function,
+// so the fused and the stand-alone paths give the same bits.
+__device__ __forceinline__ float logistic(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
+
 __device__ __forceinline__ void unpack8(const bf16x8& v, float (&f)[8]) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) f[i] = (float)v[i];

@@ -366,7 +366,7 @@ __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const bf16x8* __restric
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float z = (float)gv[e];
-      o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * (float)uv[e]);
+      o[e] = (bf16_t)(z * logistic(z) * (float)uv[e]);
     }
     a[i] = o;
   }
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16x8* g, const 
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float z = (float)gv[e], d = (float)dv[e];
-      const float s = 1.0f / (1.0f + __expf(-z));
+      const float s = logistic(z);
       og[e] = (bf16_t)(d * (float)uv[e] * s * (1.0f + z * (1.0f - s)));
       ou[e] = (bf16_t)(d * z * s);
     }
@@ -398,7 +398,7 @@ __device__ __forceinline__ bf16x8 swiglu_vec(bf16x8 gv, bf16x8 uv) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const float z = (float)gv[e];
-    o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * (float)uv[e]);
+    o[e] = (bf16_t)(z * logistic(z) * (float)uv[e]);
   }
   return o;
 }
@@ -406,7 +406,7 @@ __device__ __forceinline__ void swiglu_grad_vec(bf16x8 gv, bf16x8 uv, bf16x8 dv,
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const float z = (float)gv[e], d = (float)dv[e];
-    const float sg = 1.0f / (1.0f + __expf(-z));
+    const float sg = logistic(z);
     og[e] = (bf16_t)(d * (float)uv[e] * sg * (1.0f + z * (1.0f - sg)));
     ou[e] = (bf16_t)(d * z * sg);
   }

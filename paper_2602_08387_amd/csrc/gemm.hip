@@ -240,6 +240,7 @@ struct LoadCursor {
   __amdgpu_buffer_rsrc_t ra, rb, rb2;
   int64_t lda, ldb;
   int seg = 0, k = 0, kend = 0, nseg = 1;   // kend: K of the open segment (kept in a register: no kernarg read per K-step)
+  int left = 0;                             // K-steps of the tile still to fetch; the walk may start anywhere and wraps
 
   __device__ __forceinline__ void open_raw(const bf16_t* a, const bf16_t* b, int64_t lda_, int64_t ldb_, int K, int M,
                                            int N, int m0, int n0, int lane) {
@@ -271,7 +272,7 @@ struct LoadCursor {
   template <int C, int NC>
   __device__ __forceinline__ void issue_piece(const GemmKArgs& segs, char* stage, int wave, int m0, int n0, int lane) {
     constexpr int PA = TileLoader<BM, AK, NW>::PER_WAVE, PB = TileLoader<BN, BKM, NW>::PER_WAVE;
-    if (seg < nseg) {
+    if (left > 0) {
       la.template issue_range<C * PA / NC, (C + 1) * PA / NC>(ra, stage, wave, lda, k);
       if constexpr (PAIR)
         lb.template issue_pair_range<C * PB / NC, (C + 1) * PB / NC>(rb, rb2, stage + BM * BK * 2, wave, ldb, k);
@@ -279,18 +280,12 @@ struct LoadCursor {
         lb.template issue_perm_range<C * PB / NC, (C + 1) * PB / NC>(rb, stage + BM * BK * 2, wave, ldb, k);
       else
         lb.template issue_range<C * PB / NC, (C + 1) * PB / NC>(rb, stage + BM * BK * 2, wave, ldb, k);
-      if constexpr (C + 1 == NC) {
-        k += BK;
-        if (k == kend) {
-          k = 0;
-          if (++seg < nseg) open(segs, seg, m0, n0, lane);
-        }
-      }
+      if constexpr (C + 1 == NC) advance(segs, m0, n0, lane);
     }
   }
   // `segs`: the problem whose further K-segments follow (only read when nseg > 1)
   __device__ __forceinline__ void issue_next(const GemmKArgs& segs, char* stage, int wave, int m0, int n0, int lane) {
-    if (seg < nseg) {
+    if (left > 0) {
       la.issue(ra, stage, wave, lda, k);
       if constexpr (PAIR)
         lb.template issue_pair_range<0, TileLoader<BN, BKM, NW>::PER_WAVE>(rb, rb2, stage + BM * BK * 2, wave, ldb, k);
@@ -298,10 +293,18 @@ struct LoadCursor {
         lb.template issue_perm_range<0, TileLoader<BN, BKM, NW>::PER_WAVE>(rb, stage + BM * BK * 2, wave, ldb, k);
       else
         lb.issue(rb, stage + BM * BK * 2, wave, ldb, k);
-      k += BK;
-      if (k == kend) {
-        k = 0;
-        if (++seg < nseg) open(segs, seg, m0, n0, lane);
+      advance(segs, m0, n0, lane);
+    }
+  }
+  // one K-step on: past the end of a segment the walk goes on in the next one, past the last in the first
+  __device__ __forceinline__ void advance(const GemmKArgs& segs, int m0, int n0, int lane) {
+    --left;
+    k += BK;
+    if (k == kend) {
+      k = 0;
+      if (nseg > 1 && left > 0) {
+        seg = seg + 1 == nseg ? 0 : seg + 1;
+        open(segs, seg, m0, n0, lane);
       }
     }
   }
@@ -429,10 +432,25 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
     const int in_band = pid - band * GM * tiles_n;
     t.m0 = (first_m + in_band % band_h) * BM;
     t.n0 = (in_band / band_h) * BN;
+    // The contraction of a tile starts a (band mod 8) eighths of the way through K and wraps around.  The
+    // XCDs work on different bands at any one time, and without this they would all stream the same
+    // k-range of their operands at once: the requests then crowd the same memory channels (worst with
+    // rows a multiple of 4 KiB apart, see the down projection's weight).  The start depends on the tile's
+    // place in its problem only, so a product gives the same bits in whatever launch it is computed.
+    cur.left = t.total;
+    int first = ((band & 7) * t.total) >> 3;   // in K-steps from the start of segment 0
     cur.seg = 0;
-    cur.k = 0;
-    if constexpr (SWIGLU) cur.open_pair(a0, b0, one.b2, lda0, ldb0, K0, t.M, t.N, t.m0, t.n0, lane);
-    else cur.open_raw(a0, b0, lda0, ldb0, K0, t.M, t.N, t.m0, t.n0, lane);
+    if constexpr (!GROUPED) {
+      for (int s2 = 0; s2 + 1 < one.nseg; ++s2)
+        if (cur.seg == s2 && first >= one.K[s2] / BK) { first -= one.K[s2] / BK; cur.seg = s2 + 1; }
+    }
+    cur.k = first * BK;
+    if (cur.seg == 0) {
+      if constexpr (SWIGLU) cur.open_pair(a0, b0, one.b2, lda0, ldb0, K0, t.M, t.N, t.m0, t.n0, lane);
+      else cur.open_raw(a0, b0, lda0, ldb0, K0, t.M, t.N, t.m0, t.n0, lane);
+    } else {
+      cur.open(one, cur.seg, t.m0, t.n0, lane);
+    }
     return t;
   };
 
@@ -670,7 +688,7 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float z = (float)gq[i][e], d = acc[i][s][e];
-            const float sg = 1.0f / (1.0f + __expf(-z));
+            const float sg = logistic(z);
             gq[i][e] = (bf16_t)(d * (float)uq[i][e] * sg * (1.0f + z * (1.0f - sg)));
             uq[i][e] = (bf16_t)(d * z * sg);
           }
@@ -716,7 +734,7 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const float z = acc[i][hf * HF + jj][e];
-              o[e] = (bf16_t)(z / (1.0f + __expf(-z)) * acc[i + 2][hf * HF + jj][e]);
+              o[e] = (bf16_t)(z * logistic(z) * acc[i + 2][hf * HF + jj][e]);
             }
             *reinterpret_cast<bf16x4*>(stg + stg_off(jj, i, 0)) = o;
           }

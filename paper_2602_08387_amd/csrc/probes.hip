@@ -19,6 +19,10 @@
 //   family 2, "neighbour" (waves 0-3 of the workgroup run MFMAs only, waves 4-7, their SIMD partners, run
 //     v_fma_f32 only): variant 0 MFMA waves alone, 1 VALU waves alone, 2 together.  result[0] is then the
 //     cycles per MFMA of the MFMA waves and result[3] the cycles per fma of the VALU waves.
+//   family 3, "sustained": the operand-feed kernels of family 1 (variants 0, 1, 2) with pseudo-random operands
+//     in (-1, 1) instead of constants, launched back to back for about a second, so that the figure is
+//     the rate the matrix pipes hold at the clock the power management settles on under a long load with
+//     operands that toggle like real data.  result[1] is then the mean over all launches.
 #include "common.h"
 #include "kernels.h"
 #include <type_traits>
@@ -64,10 +68,22 @@ __global__ __launch_bounds__(NW * 64) void probe_arrangement_kernel(float* out, 
 }
 
 // R fragment reads per block of 8 MFMAs, fetched one block ahead (two register sets); TR: pairs of transposing reads
-template <int NW, int R, bool TR>
+// pseudo-random bf16 in (-1, 1) from an integer (a multiplicative hash; no statistical claims)
+__device__ __forceinline__ bf16_t probe_noise(unsigned i) {
+  i = (i + 0x9e3779b9u) * 0x85ebca6bu;
+  i ^= i >> 15;
+  i *= 0xc2b2ae35u;
+  i ^= i >> 13;
+  return (bf16_t)((float)(int)(i >> 8) * (1.0f / 8388608.0f) - 1.0f);
+}
+
+template <int NW, int R, bool TR, bool NOISE = false>
 __global__ __launch_bounds__(NW * 64) void probe_feed_kernel(float* out, long long* cyc, int iters) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  for (int i = threadIdx.x; i < 65536 / 4; i += NW * 64) ((float*)lds)[i] = 0.0f;
+  if (NOISE)
+    for (int i = threadIdx.x; i < 65536 / 2; i += NW * 64) ((bf16_t*)lds)[i] = probe_noise(blockIdx.x * 32768u + i);
+  else
+    for (int i = threadIdx.x; i < 65536 / 4; i += NW * 64) ((float*)lds)[i] = 0.0f;
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   f32x4 acc[8];
@@ -79,6 +95,12 @@ __global__ __launch_bounds__(NW * 64) void probe_feed_kernel(float* out, long lo
   for (int s = 0; s < 2; ++s)
     for (int j = 0; j < 4; ++j)
       for (int e = 0; e < 8; ++e) f[s][j][e] = (bf16_t)0.0f;
+  if (NOISE) {
+    for (int e = 0; e < 8; ++e) { b[0][e] = probe_noise(threadIdx.x * 16 + e); b[1][e] = probe_noise(threadIdx.x * 16 + 8 + e); }
+    for (int s = 0; s < 2; ++s)
+      for (int j = 0; j < 4; ++j)
+        for (int e = 0; e < 8; ++e) f[s][j][e] = probe_noise(0x10000u + threadIdx.x * 64 + s * 32 + j * 8 + e);
+  }
   const unsigned base = (unsigned)(uintptr_t)(LDS_PTR(char))lds + (wave & 7) * 8192 + lane * 16;   // 8 KB window per wave
   const long long t0 = __builtin_readcyclecounter();
   for (int it = 0; it < iters; ++it) {
@@ -158,7 +180,7 @@ constexpr int kProbeBlocks = 256, kProbeIters = 2000;
 // and fills result: cycles per block per SIMD,
 // milliseconds of the launch, shader clock in GHz (and, for the neighbour probe, the second role's figure)
 template <typename K>
-int run_probe(K kern, int nw, size_t lds, bool roles, double units_per_iter, double* result, hipStream_t st) {
+int run_probe(K kern, int nw, size_t lds, bool roles, double units_per_iter, double* result, hipStream_t st, int launches = 1) {
   float* out = nullptr;
   long long* cyc = nullptr;
   if (hipMalloc(&out, (size_t)kProbeBlocks * nw * 64 * sizeof(float)) != hipSuccess) return fail(-3, "probe: out of device memory");
@@ -166,21 +188,25 @@ int run_probe(K kern, int nw, size_t lds, bool roles, double units_per_iter, dou
     (void)hipFree(out);
     return fail(-3, "probe: out of device memory");
   }
-  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr, e2 = nullptr;
   int rc = 0;
-  float ms = 0.f;
+  float ms = 0.f, ms_all = 0.f;
   static long long host[kProbeBlocks * 8];
   if (lds && hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
     rc = fail(-3, "probe: cannot reserve LDS");
-  if (!rc && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) rc = fail(-3, "probe: no events");
+  if (!rc && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess || hipEventCreate(&e2) != hipSuccess))
+    rc = fail(-3, "probe: no events");
   if (!rc) {
     hipLaunchKernelGGL(kern, dim3(kProbeBlocks), dim3(nw * 64), lds, st, out, cyc, 10);   // warm-up
+    (void)hipEventRecord(e2, st);
+    for (int l = 1; l < launches; ++l) hipLaunchKernelGGL(kern, dim3(kProbeBlocks), dim3(nw * 64), lds, st, out, cyc, kProbeIters);
     (void)hipEventRecord(e0, st);
-    hipLaunchKernelGGL(kern, dim3(kProbeBlocks), dim3(nw * 64), lds, st, out, cyc, kProbeIters);
+    hipLaunchKernelGGL(kern, dim3(kProbeBlocks), dim3(nw * 64), lds, st, out, cyc, kProbeIters);   // the launch the cycle counts are of
     (void)hipEventRecord(e1, st);
     rc = check_launch("probe");
     if (!rc && hipEventSynchronize(e1) != hipSuccess) rc = fail(-3, "probe: synchronisation failed");
     if (!rc && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = fail(-3, "probe: no elapsed time");
+    if (!rc && hipEventElapsedTime(&ms_all, e2, e1) != hipSuccess) rc = fail(-3, "probe: no elapsed time");
     if (!rc && hipMemcpy(host, cyc, (size_t)kProbeBlocks * nw * sizeof(long long), hipMemcpyDeviceToHost) != hipSuccess)
       rc = fail(-3, "probe: copy failed");
   }
@@ -203,12 +229,13 @@ int run_probe(K kern, int nw, size_t lds, bool roles, double units_per_iter, dou
     second /= kProbeBlocks;
     const double waves_per_simd = roles ? 1.0 : nw / 4.0;
     result[0] = first / (kProbeIters * units_per_iter) / waves_per_simd;
-    result[1] = ms;
+    result[1] = launches > 1 ? ms_all / launches : ms;
     result[2] = longest / (ms * 1e6);
     result[3] = roles ? second / (kProbeIters * 64.0) : 0.0;
   }
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
+  if (e2) (void)hipEventDestroy(e2);
   (void)hipFree(out);
   (void)hipFree(cyc);
   return rc;
@@ -234,6 +261,16 @@ int feed(int variant, double* result, hipStream_t st) {
   }
   return fail(-1, "probe: feed variant %d", variant);
 }
+constexpr int kSustainedLaunches = 2500;   // about a second of back-to-back launches
+template <int NW>
+int sustained(int variant, double* result, hipStream_t st) {
+  switch (variant) {
+    case 0: return run_probe(probe_feed_kernel<NW, 0, false, true>, NW, 65536, false, 2.0, result, st, kSustainedLaunches);
+    case 1: return run_probe(probe_feed_kernel<NW, 2, false, true>, NW, 65536, false, 2.0, result, st, kSustainedLaunches);
+    case 2: return run_probe(probe_feed_kernel<NW, 3, false, true>, NW, 65536, false, 2.0, result, st, kSustainedLaunches);
+  }
+  return fail(-1, "probe: sustained variant %d", variant);
+}
 
 }  // namespace
 
@@ -250,6 +287,7 @@ int launch_probe(int family, int variant, int waves_per_simd, double* result, hi
   if (waves_per_simd != 1 && waves_per_simd != 2) return fail(-1, "probe: 1 or 2 waves per SIMD, got %d", waves_per_simd);
   if (family == 0) return waves_per_simd == 1 ? arrangement<4>(variant, result, st) : arrangement<8>(variant, result, st);
   if (family == 1) return waves_per_simd == 1 ? feed<4>(variant, result, st) : feed<8>(variant, result, st);
+  if (family == 3) return waves_per_simd == 1 ? sustained<4>(variant, result, st) : sustained<8>(variant, result, st);
   return fail(-1, "probe: family %d", family);
 }
 

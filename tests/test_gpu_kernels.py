@@ -522,7 +522,12 @@ def test_issue_rate_probe_reports_the_matrix_pipe_rate(K):
         assert ms > 0.0 and 0.5 < ghz < 3.0, (ms, ghz)
     both = K.issue_rate_probe(0, 2, 2)[0]
     assert 512.0 <= both < 1024.0      # VALU work next to the MFMAs costs something, less than running it after them
+    # sustained family: 8 MFMAs 16x16x32 of 16 cycles each per block; a long run may be clocked down, never sped up
+    cycles, ms, ghz, _ = K.issue_rate_probe(3, 0, 2)
+    assert 128.0 <= cycles < 160.0 and ms > 0.0 and 0.5 < ghz < 3.0, (cycles, ms, ghz)
     with pytest.raises(K.DLayerError):
-        K.issue_rate_probe(3, 0, 2)
+        K.issue_rate_probe(4, 0, 2)
+    with pytest.raises(K.DLayerError):
+        K.issue_rate_probe(3, 3, 2)
     with pytest.raises(K.DLayerError):
         K.issue_rate_probe(0, 0, 3)
