@@ -143,7 +143,10 @@ def test_swiglu(K):
     # several tiles per workgroup with an odd number of K-steps (3, 1, 5): the ring stage a tile starts
     # in alternates from tile to tile; with one K-step the next tile's loads go out after the loop,
     # with two they go out during the very first K-step.  The last one runs on the 128 x 128 tiles.
-    (8192, 192, 4096, False), (8192, 64, 4096, True), (8192, 128, 4200, False), (2048, 320, 5000, True)])
+    (8192, 192, 4096, False), (8192, 64, 4096, True), (8192, 128, 4200, False), (2048, 320, 5000, True),
+    # more than 8 bands of 8 tile-rows and 7 K-steps: a tile's contraction starts (band mod 8) * 7 / 8 K-steps
+    # in and wraps; 256 x 256 tiles (10 bands) and 128 x 128 tiles (18 bands)
+    (20480, 448, 768, True), (18432, 448, 512, False)])
 def test_linear_forward(K, T, Kd, N, res):
     rng = np.random.default_rng(T + N)
     xb, wb, rb = _rand_bits(rng, (T, Kd)), _rand_bits(rng, (N, Kd), 0.05), _rand_bits(rng, (T, N))

@@ -65,7 +65,9 @@ def _check_layer(g, f, r, tag, y_tol=REL_TOL):
     ("1b", {"batch": 1, "seq": 512, "rope_layout": 1}),
     # many tokens, narrow layer: every product has more tiles than workgroups and an odd number of
     # K-steps per segment (5, 5, 5 for the q/k/v input gradients, 7 + 7 for gate/up), so the
-    # persistent GEMMs change their ring parity from tile to tile and across K-segments
+    # persistent GEMMs change their ring parity from tile to tile and across K-segments; with 16 bands of
+    # 8 tile-rows the contraction of a tile starts at every K-step offset of every segment in turn
+    # (q/k/v: K-steps 0, 1, 3, 5, 7, 9, 11, 13 of 15; gate/up: 0, 1, 3, 5, 7, 8, 10, 12 of 14) and wraps
     # a layer wider than 4096 (70B-like proportions, few tokens)
     ("tiny", {"seq": 256, "d_model": 8192, "n_q_heads": 8, "n_kv_heads": 2, "head_dim": 128, "d_ff": 1024}),
     ("tiny", {"batch": 16, "seq": 2048, "d_model": 320, "n_q_heads": 5, "n_kv_heads": 5, "head_dim": 64, "d_ff": 448}),
