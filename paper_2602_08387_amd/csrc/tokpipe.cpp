@@ -112,7 +112,7 @@ bool load_index(const char* path, std::vector<Span>& docs) {
   if (!m.open(path) || m.n < 16 || memcmp(m.p, kIdxMagic, 8) != 0) return false;
   uint64_t n;
   memcpy(&n, m.p + 8, 8);
-  if (m.n != 16 + n * 16) return false;
+  if (n > (m.n - 16) / 16 || m.n != 16 + n * 16) return false;   // the first test keeps n * 16 from wrapping
   docs.resize(n);
   if (n) memcpy(docs.data(), m.p + 16, n * 16);
   return true;
@@ -559,7 +559,8 @@ int tokpipe_tokenize(const char* jsonl_path, const char* index_path, const char*
   struct stat st;
   if (fstat(in_fd, &st) != 0) { ::close(in_fd); return fail("tokpipe_tokenize: cannot stat %s", jsonl_path); }
   for (size_t d = 0; d < docs.size(); ++d)
-    if (docs[d].off + docs[d].len > (uint64_t)st.st_size || (d && docs[d].off < docs[d - 1].off + docs[d - 1].len)) {
+    if (docs[d].len > (uint64_t)st.st_size || docs[d].off > (uint64_t)st.st_size - docs[d].len ||
+        (d && docs[d].off < docs[d - 1].off + docs[d - 1].len)) {
       ::close(in_fd);
       return fail("tokpipe_tokenize: index entry %zu does not fit %s", d, jsonl_path);
     }
@@ -719,8 +720,9 @@ tokfile* tokfile_open(const char* path) {
   memcpy(&f->n_docs, f->map.p + 16, 8);
   memcpy(&f->n_tokens, f->map.p + 24, 8);
   memcpy(&index_off, f->map.p + 32, 8);
-  if (version != 1 || (f->token_bytes != 2 && f->token_bytes != 4) || index_off % 8 || index_off < kHeader + f->n_tokens * f->token_bytes ||
-      f->map.n < index_off + (f->n_docs + 1) * 8) {
+  // sizes are compared by division so that a corrupt header cannot wrap a product
+  if (version != 1 || (f->token_bytes != 2 && f->token_bytes != 4) || index_off % 8 || index_off < kHeader || index_off > f->map.n ||
+      f->n_tokens > (index_off - kHeader) / f->token_bytes || f->n_docs >= (f->map.n - index_off) / 8) {
     fail("tokfile_open: %s has an inconsistent header", path);
     return nullptr;
   }

@@ -122,3 +122,39 @@ def test_errors_name_the_document_and_leave_no_hang(tmp_path):
         tp.tokenize(tmp_path / "b.jsonl", tmp_path / "b.idx", tmp_path / "o", [], "text", n_workers=0)
     with pytest.raises(tp.TokPipeError):
         tp.TokenFile(tmp_path / "b.jsonl")
+
+
+def test_corrupt_index_and_token_files_are_rejected(tmp_path):
+    """Counts and offsets in a file header are untrusted: values chosen so that count * size wraps around
+    64 bits, or so that a range ends past the file, must give an error, never a crash or a huge allocation."""
+    import struct
+    src, idx, out = tmp_path / "c.jsonl", tmp_path / "c.idx", tmp_path / "c.tok"
+    src.write_bytes(b'{"text": "one two"}\n{"text": "three"}\n')
+    tp.index_jsonl(src, idx, 1)
+    tp.tokenize(src, idx, out, [], "text", -1)
+    good_idx, good_tok = idx.read_bytes(), out.read_bytes()
+    # index: a document count whose byte size wraps to the true payload size; an entry past the end of the file;
+    # an offset + length that wraps; entries out of order
+    n = struct.unpack("<Q", good_idx[8:16])[0]
+    cases = [
+        good_idx[:8] + struct.pack("<Q", n + (1 << 60)) + good_idx[16:],
+        good_idx[:16] + struct.pack("<QQ", 0, 1 << 40) + good_idx[32:],
+        good_idx[:16] + struct.pack("<QQ", (1 << 64) - 4, 8) + good_idx[32:],
+        good_idx[:16] + good_idx[32:48] + good_idx[16:32],
+    ]
+    for raw in cases:
+        bad = tmp_path / "bad.idx"
+        bad.write_bytes(raw)
+        with pytest.raises(tp.TokPipeError):
+            tp.tokenize(src, bad, tmp_path / "o.tok", [], "text", -1)
+    # token file: header fields 16 (documents), 24 (tokens), 32 (index offset)
+    def patched(at, value):
+        return good_tok[:at] + struct.pack("<Q", value) + good_tok[at + 8:]
+    for raw in (patched(16, (1 << 61) - 1), patched(16, 3), patched(24, 1 << 63), patched(24, 1 << 40),
+                patched(32, 8), patched(32, len(good_tok) + 8), patched(32, 1 << 62), good_tok[:40]):
+        bad = tmp_path / "bad.tok"
+        bad.write_bytes(raw)
+        with pytest.raises(tp.TokPipeError):
+            tp.TokenFile(bad)
+    with tp.TokenFile(out) as f:                       # the untouched file still opens
+        assert f.num_docs == 2
