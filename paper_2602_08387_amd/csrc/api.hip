@@ -49,6 +49,12 @@ static int check_device() {
 
 static inline size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
 
+// rows * cols bf16 elements stay below 4 GiB (what a buffer descriptor's 32-bit byte count and the kernels'
+// 32-bit byte offsets can address); the dimensions are bounded first so that the product cannot wrap
+static inline bool under_4gib(int64_t rows, int64_t cols) {
+  return rows >= 0 && cols >= 0 && rows < ((int64_t)1 << 31) && cols < ((int64_t)1 << 31) && rows * cols * 2 < ((int64_t)1 << 32);
+}
+
 struct Carver {
   char* base;
   size_t off = 0;
@@ -77,12 +83,12 @@ static const char* cfg_problem(const dlayer_cfg* c) {
   if (c->recompute & ~(DLAYER_RECOMPUTE_NORMS | DLAYER_RECOMPUTE_SWIGLU)) return "unknown recompute bits";
   if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return "rms_eps must be >= 0 and rope_base > 0";
   const int64_t T = (int64_t)c->batch * c->seq;
-  const int64_t widest = padded_ff(c) > c->n_q_heads * c->head_dim ? padded_ff(c) : (int64_t)c->n_q_heads * c->head_dim;
-  if (T * widest * 2 >= ((int64_t)1 << 32) || T * c->d_model * 2 >= ((int64_t)1 << 32))
+  const int64_t widest = padded_ff(c) > (int64_t)c->n_q_heads * c->head_dim ? padded_ff(c) : (int64_t)c->n_q_heads * c->head_dim;
+  if (!under_4gib(T, widest) || !under_4gib(T, c->d_model))
     return "an activation tensor reaches 4 GiB";
   // the weights (and their transposed copies, whose d_ff rows are padded) are addressed with 32-bit byte offsets too
   const int64_t D = c->d_model, QD = (int64_t)c->n_q_heads * c->head_dim;
-  if (padded_ff(c) * D * 2 >= ((int64_t)1 << 32) || QD * D * 2 >= ((int64_t)1 << 32))
+  if (!under_4gib(padded_ff(c), D) || !under_4gib(QD, D))
     return "a weight tensor reaches 4 GiB";
   return nullptr;
 }
@@ -387,7 +393,7 @@ int lm_head_ce_fwd_bwd(const void* h, const void* w_lm, const int64_t* targets, 
           "lm_head_ce_fwd_bwd: T, D and V must be positive multiples of 64");
   REQUIRE(chunk_rows >= 0 && chunk_rows % 64 == 0, "lm_head_ce_fwd_bwd: chunk_rows must be 0 or a multiple of 64");
   const int64_t Tc = lm_head_chunk(T, V, chunk_rows);
-  REQUIRE(T * D * 2 < ((int64_t)1 << 32) && V * D * 2 < ((int64_t)1 << 32) && Tc * V * 2 < ((int64_t)1 << 32) &&
+  REQUIRE(under_4gib(T, D) && under_4gib(V, D) && under_4gib(Tc, V) &&
               T < ((int64_t)1 << 31),
           "lm_head_ce_fwd_bwd: an operand (or a chunk of logits) reaches 4 GiB");
   REQUIRE_PTR(h); REQUIRE_PTR(w_lm); REQUIRE_PTR(dh); REQUIRE_PTR(dw_lm); REQUIRE_PTR(workspace);
@@ -438,7 +444,7 @@ int rmsnorm_backward(const void* x, const void* gamma, const float* rstd, const 
 int linear_forward(const void* x, const void* w, const void* residual, int64_t T, int64_t K, int64_t N, void* y,
                    void* stream) {
   REQUIRE(T > 0 && K > 0 && N > 0 && K % 64 == 0 && N % 8 == 0, "linear_forward: need K %% 64 == 0 and N %% 8 == 0");
-  REQUIRE(T * K * 2 < ((int64_t)1 << 32) && N * K * 2 < ((int64_t)1 << 32) && T < (1 << 30) && N < (1 << 30),
+  REQUIRE(under_4gib(T, K) && under_4gib(N, K) && T < (1 << 30) && N < (1 << 30),
           "linear_forward: an operand reaches 4 GiB");
   REQUIRE_PTR(x); REQUIRE_PTR(w); REQUIRE_PTR(y);
   REQUIRE(residual == nullptr || aligned16(residual), "linear_forward: residual is misaligned");
@@ -460,8 +466,8 @@ int qkv_rope_forward(const void* h, const void* wq, const void* wk, const void* 
   REQUIRE(rope_layout == 0 || rope_layout == 1, "qkv_rope_forward: rope_layout must be 0 or 1");
   REQUIRE(rope_base > 0.f, "qkv_rope_forward: rope_base must be positive");
   const int64_t T = batch * seq, QD = n_q_heads * head_dim, KD = n_kv_heads * head_dim;
-  REQUIRE(T * d_model * 2 < ((int64_t)1 << 32) && QD * d_model * 2 < ((int64_t)1 << 32) && T * QD * 2 < ((int64_t)1 << 32) &&
-              KD * d_model * 2 < ((int64_t)1 << 32) && T * KD * 2 < ((int64_t)1 << 32),
+  REQUIRE(under_4gib(T, d_model) && under_4gib(QD, d_model) && under_4gib(T, QD) &&
+              under_4gib(KD, d_model) && under_4gib(T, KD),
           "qkv_rope_forward: an operand reaches 4 GiB");
   REQUIRE_PTR(h); REQUIRE_PTR(wq); REQUIRE_PTR(wk); REQUIRE_PTR(wv); REQUIRE_PTR(q); REQUIRE_PTR(k); REQUIRE_PTR(v);
   REQUIRE_PTR(workspace);
@@ -481,7 +487,7 @@ int linear_swiglu_forward(const void* x, const void* w_gate, const void* w_up, i
                           void* g, void* u, void* a, void* stream) {
   REQUIRE(T > 0 && K > 0 && F > 0 && K % 64 == 0 && F % 8 == 0,
           "linear_swiglu_forward: need K %% 64 == 0 and F %% 8 == 0");
-  REQUIRE(T * K * 2 < ((int64_t)1 << 32) && F * K * 2 < ((int64_t)1 << 32) && T < (1 << 30) && F < (1 << 29),
+  REQUIRE(under_4gib(T, K) && under_4gib(F, K) && T < (1 << 30) && F < (1 << 29),
           "linear_swiglu_forward: an operand reaches 4 GiB");
   REQUIRE_PTR(x); REQUIRE_PTR(w_gate); REQUIRE_PTR(w_up); REQUIRE_PTR(g); REQUIRE_PTR(u); REQUIRE_PTR(a);
   TRY(check_device());
@@ -496,7 +502,7 @@ int linear_backward(const void* x, const void* w, const void* dy, int64_t T, int
                     void* dw, int accumulate_dw, void* workspace, void* stream) {
   REQUIRE(T > 0 && K > 0 && N > 0 && T % 64 == 0 && K % 64 == 0 && N % 64 == 0,
           "linear_backward: T, K and N must be multiples of 64");
-  REQUIRE(T * K * 2 < ((int64_t)1 << 32) && N * K * 2 < ((int64_t)1 << 32) && T * N * 2 < ((int64_t)1 << 32),
+  REQUIRE(under_4gib(T, K) && under_4gib(N, K) && under_4gib(T, N),
           "linear_backward: an operand reaches 4 GiB");
   REQUIRE_PTR(x); REQUIRE_PTR(w); REQUIRE_PTR(dy);
   REQUIRE((dx == nullptr || aligned16(dx)) && (dw == nullptr || aligned16(dw)), "linear_backward: misaligned output");
@@ -520,7 +526,7 @@ int linear_swiglu_backward(const void* dy, const void* w_down, const void* g, co
                            int64_t F, void* dg, void* du, void* workspace, void* stream) {
   REQUIRE(T > 0 && D > 0 && F > 0 && T % 64 == 0 && D % 64 == 0 && F % 64 == 0,
           "linear_swiglu_backward: T, D and F must be multiples of 64");
-  REQUIRE(T * D * 2 < ((int64_t)1 << 32) && D * F * 2 < ((int64_t)1 << 32) && T * F * 2 < ((int64_t)1 << 32),
+  REQUIRE(under_4gib(T, D) && under_4gib(D, F) && under_4gib(T, F),
           "linear_swiglu_backward: an operand reaches 4 GiB");
   REQUIRE_PTR(dy); REQUIRE_PTR(w_down); REQUIRE_PTR(g); REQUIRE_PTR(u); REQUIRE_PTR(dg); REQUIRE_PTR(du);
   REQUIRE_PTR(workspace);
@@ -539,7 +545,7 @@ int linear_wgrad_group(int32_t n, const void* const* dy, const void* const* x, c
   for (int i = 0; i < n; ++i) {
     REQUIRE(N[i] > 0 && K[i] > 0 && N[i] % 64 == 0 && K[i] % 64 == 0,
             "linear_wgrad_group: N[%d] and K[%d] must be positive multiples of 64", i, i);
-    REQUIRE(T * K[i] * 2 < ((int64_t)1 << 32) && N[i] * K[i] * 2 < ((int64_t)1 << 32) && T * N[i] * 2 < ((int64_t)1 << 32),
+    REQUIRE(under_4gib(T, K[i]) && under_4gib(N[i], K[i]) && under_4gib(T, N[i]),
             "linear_wgrad_group: an operand of product %d reaches 4 GiB", i);
     REQUIRE(dy[i] && x[i] && dw[i] && aligned16(dy[i]) && aligned16(x[i]) && aligned16(dw[i]),
             "linear_wgrad_group: a pointer of product %d is null or not 16-byte aligned", i);
@@ -565,7 +571,7 @@ static int attn_shape_ok(int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t 
   REQUIRE(dh == 32 || dh == 64 || dh == 128, "%s: head_dim must be 32, 64 or 128", who);
   REQUIRE(Hq % Hkv == 0, "%s: n_q_heads must be a multiple of n_kv_heads", who);
   REQUIRE(S % 128 == 0, "%s: seq must be a multiple of 128", who);
-  REQUIRE(B * S * Hq * dh * 2 < ((int64_t)1 << 32), "%s: q reaches 4 GiB", who);
+  REQUIRE(under_4gib(B, S) && under_4gib(Hq, dh) && under_4gib(B * S, Hq * dh), "%s: q reaches 4 GiB", who);
   REQUIRE(B < 65536 && Hq < 65536, "%s: batch or head count too large", who);
   return 0;
 }

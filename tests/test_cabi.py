@@ -44,7 +44,10 @@ def test_size_queries_and_cfg_validation_on_host():
     for bad in (cfg.with_(head_dim=96), cfg.with_(n_kv_heads=5), cfg.with_(seq=100), cfg.with_(d_ff=1000),
                 cfg.with_(rope_layout=2), cfg.with_(batch=0), cfg.with_(d_model=16448),
                 # few tokens, but w_gate alone is 16384 x 131072 x 2 B = 4 GiB
-                cfg.with_(batch=1, seq=128, d_model=16384, d_ff=131072, n_q_heads=8, n_kv_heads=8)):
+                cfg.with_(batch=1, seq=128, d_model=16384, d_ff=131072, n_q_heads=8, n_kv_heads=8),
+                # batch * seq * width * 2 wraps around 64 bits to a small number: still too large
+                cfg.with_(batch=2 ** 31 - 1, seq=2 ** 31 - 128, d_model=4096),
+                cfg.with_(batch=2 ** 20, seq=2 ** 22)):
         assert K.dlayer_saved_bytes(bad) == 0 and K.dlayer_workspace_bytes(bad) == 0
     assert K.ce_loss_workspace_bytes(8192, 128256) == 8192 * 4
     assert K.rmsnorm_backward_workspace_bytes(16384, 4096) == 512 * 4096 * 4
