@@ -59,6 +59,7 @@ struct GemmKArgs {
   const bf16_t* r;
   int accumulate;
   int tiles_m, tiles_n;
+  int band_rows;   // tile rows per band of the tile sequence (see band_rows_for)
   // gated-pair products only (see gemm_swiglu_kernel): second weight, second and third output
   const bf16_t* b2;
   bf16_t *c2, *c3;
@@ -396,16 +397,16 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
   static_assert(!PERM || (EPI == EPI_ROPE && AK && BKM && BN % 128 == 0), "partner-order tiles: rotary epilogue only");
 
   // tile id -> tile origin, and the load cursor opened on the tile's first K-segment.  The tile
-  // sequence of a problem runs in bands of 8 tile-rows, so that the ~32 consecutive tiles an XCD holds
-  // at a time share A and B panels.
+  // sequence of a problem runs in bands of band_rows (8 or 4) tile-rows, so that the ~32 consecutive
+  // tiles an XCD holds at a time share A and B panels.
   auto locate = [&](int id) {
     int pid = xcd_contiguous(id, ntiles);
-    int tiles_m, tiles_n, K0, start = 0;
+    int tiles_m, tiles_n, K0, GM, start = 0;
     const bf16_t *a0, *b0;
     int64_t lda0, ldb0;
     Tile t;
     auto take = [&](const GemmKArgs& q) {
-      tiles_m = q.tiles_m; tiles_n = q.tiles_n; K0 = q.K[0];
+      tiles_m = q.tiles_m; tiles_n = q.tiles_n; K0 = q.K[0]; GM = q.band_rows > 0 ? q.band_rows : 8;
       a0 = q.a[0]; b0 = q.b[0]; lda0 = q.lda[0]; ldb0 = q.ldb[0];
       t.M = q.M; t.N = q.N; t.accumulate = q.accumulate; t.c = q.c; t.r = q.r; t.ldc = q.ldc;
       t.rope = EPI == EPI_ROPE ? q.rope : 0;
@@ -425,20 +426,20 @@ __device__ __forceinline__ void gemm_persistent(const GemmGroupKArgs& grp, const
       t.total = 0;
       for (int s2 = 0; s2 < one.nseg; ++s2) t.total += one.K[s2] / BK;
     }
-    constexpr int GM = 8;
     const int band = pid / (GM * tiles_n);
     const int first_m = band * GM;
     const int band_h = min(tiles_m - first_m, GM);
     const int in_band = pid - band * GM * tiles_n;
     t.m0 = (first_m + in_band % band_h) * BM;
     t.n0 = (in_band / band_h) * BN;
-    // The contraction of a tile starts a (band mod 8) eighths of the way through K and wraps around.  The
-    // XCDs work on different bands at any one time, and without this they would all stream the same
-    // k-range of their operands at once: the requests then crowd the same memory channels (worst with
-    // rows a multiple of 4 KiB apart, see the down projection's weight).  The start depends on the tile's
-    // place in its problem only, so a product gives the same bits in whatever launch it is computed.
+    // The contraction of a tile starts (g mod 8) eighths of the way through K and wraps around, g = the
+    // tile's group of 8 tile-rows.  The XCDs work on different groups at any one time, and without this
+    // they would all stream the same k-range of their operands at once: the requests then crowd the
+    // same memory channels (worst with rows a multiple of 4 KiB apart, see the down projection's
+    // weight).  The start depends on the tile's rows only - not on the workgroup, the launch or the band
+    // height - so a product gives the same bits in whatever launch it is computed.
     cur.left = t.total;
-    int first = ((band & 7) * t.total) >> 3;   // in K-steps from the start of segment 0
+    int first = (((t.m0 / (8 * BM)) & 7) * t.total) >> 3;   // in K-steps from the start of segment 0
     cur.seg = 0;
     if constexpr (!GROUPED) {
       for (int s2 = 0; s2 + 1 < one.nseg; ++s2)
@@ -877,6 +878,17 @@ __global__ __launch_bounds__(WM* WN * 64, WM* WN == 4 ? 2 : 1) void gemm_group_r
   gemm_persistent<true, BM, BN, WM, WN, true, true, EPI_ROPE, PERM>(g, g.prob[0]);
 }
 
+// Tile rows per band of the tile sequence.  An XCD runs some 32 consecutive tiles at a time: 8 rows x 4
+// columns of tiles with bands of 8, 4 x 8 with bands of 4 - twelve operand panels either way, but the
+// wider arrangement touches longer runs of every C row (and of the g, u rows the activation-gradient
+// epilogue reads).  Measured at the 8B shape, per launch: bands of 8 are 1-2.5 % faster for k-major
+// products with K <= 4096 (q/k/v, o, gate/up forward, o input gradient), bands of 4 are 1-4 % faster for
+// the long contractions (down projection, fused input gradients: +6-8 % at K = 8192), the
+// activation-gradient epilogue and the weight gradients; bands of 2 or 16 lose everywhere.
+static int band_rows_for(bool both_kmajor, int64_t k_total, bool epilogue_reads_tiles) {
+  return both_kmajor && !epilogue_reads_tiles && k_total <= 4096 ? 8 : 4;
+}
+
 // As many workgroups as the LDS lets a CU hold at once (one for the 256 x 256 tile's 160 KB, two for
 // the 128 x 128 tile's 72 KB, which then also gives every SIMD a second wave), fewer if there are fewer
 // tiles.
@@ -908,6 +920,7 @@ static int launch_group_cfg(const GemmKArgs* ks, int n, bool ak, bool bk, const 
   for (int i = 0; i < n; ++i) {
     g.prob[i] = ks[i];
     g.prob[i].tiles_m = (ks[i].M + BM - 1) / BM;
+    g.prob[i].band_rows = band_rows_for(ak && bk, ks[i].K[0], false);
     g.prob[i].tiles_n = (ks[i].N + BN - 1) / BN;
     g.tile_start[i + 1] = g.tile_start[i] + g.prob[i].tiles_m * g.prob[i].tiles_n;
   }
@@ -949,6 +962,9 @@ template <int BM, int BN, int WM, int WN>
 static int launch_cfg(const GemmKArgs& k, bool ak, bool bk, hipStream_t st) {
   GemmKArgs a = k;
   a.tiles_m = (k.M + BM - 1) / BM;
+  int64_t k_total = 0;
+  for (int s = 0; s < k.nseg; ++s) k_total += k.K[s];
+  a.band_rows = band_rows_for(ak && bk, k_total, false);
   a.tiles_n = (k.N + BN - 1) / BN;
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
   const dim3 grid((unsigned)persistent_grid(a.tiles_m * a.tiles_n, lds)), block(WM * WN * 64);
@@ -1007,6 +1023,7 @@ static int launch_fused(GemmKArgs k, const char* what, hipStream_t st) {
   constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
   k.nseg = 1;
   k.tiles_m = (k.M + BM - 1) / BM;
+  k.band_rows = band_rows_for(true, k.K[0], EPI == EPI_SWIGLU_GRAD);
   k.tiles_n = (k.N + BN - 1) / BN;
   const size_t lds = lds_bytes<BM, BN>(WM * WN, WM);
   const dim3 grid((unsigned)persistent_grid(k.tiles_m * k.tiles_n, lds)), block(WM * WN * 64);
