@@ -682,6 +682,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(
   __syncthreads();
   int stage = 0;
   for (int it = 0; it < niter; ++it) {
+    // The K fragments are pinned in registers across the loads below.  The kernel is a few registers
+    // short, and left alone the compiler spills one K fragment and reloads it at the top of the loop:
+    // vmcnt counts in order, so the wait for that reload also waits for the tile loads issued just
+    // before it, every iteration (-7 % on the backward at S = 2048; at S = 8192, where the kernels run
+    // at the power limit, the other workgroup's waves cover the stall and nothing changes).  With the
+    // pin the spill moves to values whose reload comes after the first two products.
+    static_assert(DH == 128 || DH == 64, "the pin lists the DH / 16 fragments by name");
+    if constexpr (DH == 128)
+      asm volatile("" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7]));
+    else
+      asm volatile("" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]));
     if (it + 1 < niter) issue_tile(stage ^ 1);
     const int qrow = cur_qt * 32;
     if (++cur_g == G) { cur_g = 0; --cur_qt; }
