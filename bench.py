@@ -311,6 +311,7 @@ PROBES = (
     (3, 0, "sustained, random operands: 16x16x32 MFMAs, operands in registers"),
     (3, 1, "sustained, random operands:   with 2 ds_read_b128 per 8 MFMAs"),
     (3, 2, "sustained, random operands:   with 3 ds_read_b128 per 8 MFMAs"),
+    (3, 3, "sustained, random operands: 32x32x16 MFMAs, operands in registers"),
 )
 
 
@@ -320,8 +321,9 @@ def run_probes(K):
     for fam, var, label in PROBES:
         for wps in (1, 2):
             cyc, ms, ghz, _ = K.issue_rate_probe(fam, var, wps)
-            mfmas = 0 if (fam, var) == (0, 1) else 256 * 4 * wps * 2000 * (16 if fam == 0 else 8 * 2)
-            flop = mfmas * (32768.0 if fam == 0 else 16384.0)
+            big = fam == 0 or (fam, var) == (3, 3)     # blocks of 16 MFMAs 32x32x16, else 2 x 8 MFMAs 16x16x32 per iteration
+            mfmas = 0 if (fam, var) == (0, 1) else 256 * 4 * wps * 2000 * (16 if big else 8 * 2)
+            flop = mfmas * (32768.0 if big else 16384.0)
             rows.append({"probe": label, "waves_per_simd": wps, "cycles_per_block_per_simd": round(cyc, 1),
                          "ms": round(ms, 3), "shader_ghz": round(ghz, 2), "mfma_tflops": round(flop / ms / 1e9, 0)})
     for var, label in ((0, "MFMA waves alone"), (1, "VALU waves alone"), (2, "MFMA waves and VALU waves side by side")):

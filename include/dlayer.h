@@ -324,7 +324,8 @@ int adamw_step(int32_t n, void* const* params, const void* const* grads, float* 
  *             ignored): variant 0 the MFMA waves alone, 1 the VALU waves alone, 2 both
  *   family 3  family 1's variants 0, 1, 2 with pseudo-random operands in (-1, 1) instead of constants,
  *             2500 launches back to back (about a second): the rate the matrix pipes hold at the clock
- *             the power management settles on under a long load; the milliseconds are the mean launch
+ *             the power management settles on under a long load; the milliseconds are the mean launch;
+ *             variant 3: the 32x32x16 MFMAs of family 0, variant 0, the same way (block = 16 MFMAs)
  * waves_per_simd: 1 or 2.  result (host, 4 doubles): shader-clock cycles per block per SIMD (family 2:
  * per MFMA of an MFMA wave), milliseconds of the launch, shader clock in GHz during it, and for family
  * 2 the cycles per fma of a VALU wave (else 0).  Allocates and frees a few KB of device memory and

@@ -22,7 +22,8 @@
 //   family 3, "sustained": the operand-feed kernels of family 1 (variants 0, 1, 2) with pseudo-random operands
 //     in (-1, 1) instead of constants, launched back to back for about a second, so that the figure is
 //     the rate the matrix pipes hold at the clock the power management settles on under a long load with
-//     operands that toggle like real data.  result[1] is then the mean over all launches.
+//     operands that toggle like real data.  result[1] is then the mean over all launches.  Variant 3: the
+//     32x32x16 MFMAs of family 0, variant 0, the same way (one block = 16 MFMAs).
 #include "common.h"
 #include "kernels.h"
 #include <type_traits>
@@ -37,7 +38,16 @@ __device__ __forceinline__ void probe_valu(float (&x)[8], float (&y)[8], int j, 
   for (int v = 0; v < nf; ++v) asm volatile("v_fma_f32 %0, %0, %1, %1" : "+v"(x[(j * nf + v) & 7]) : "v"(y[(j * nf + v + 3) & 7]));
 }
 
-template <int NW, int VARIANT>
+// pseudo-random bf16 in (-1, 1) from an integer (a multiplicative hash; no statistical claims)
+__device__ __forceinline__ bf16_t probe_noise(unsigned i) {
+  i = (i + 0x9e3779b9u) * 0x85ebca6bu;
+  i ^= i >> 15;
+  i *= 0xc2b2ae35u;
+  i ^= i >> 13;
+  return (bf16_t)((float)(int)(i >> 8) * (1.0f / 8388608.0f) - 1.0f);
+}
+
+template <int NW, int VARIANT, bool NOISE = false>
 __global__ __launch_bounds__(NW * 64) void probe_arrangement_kernel(float* out, long long* cyc, int iters) {
   const int lane = threadIdx.x & 63;
   f32x16 acc[4];
@@ -45,6 +55,8 @@ __global__ __launch_bounds__(NW * 64) void probe_arrangement_kernel(float* out, 
     for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
   bf16x8 a, b;
   for (int e = 0; e < 8; ++e) { a[e] = (bf16_t)1.0f; b[e] = (bf16_t)(float)(lane & 1); }
+  if (NOISE)
+    for (int e = 0; e < 8; ++e) { a[e] = probe_noise(threadIdx.x * 16 + e); b[e] = probe_noise(threadIdx.x * 16 + 8 + e); }
   float x[8], y[8];
   for (int i = 0; i < 8; ++i) { x[i] = (float)(lane + i) * 1e-3f; y[i] = -(float)i; }
   __syncthreads();
@@ -68,15 +80,6 @@ __global__ __launch_bounds__(NW * 64) void probe_arrangement_kernel(float* out, 
 }
 
 // R fragment reads per block of 8 MFMAs, fetched one block ahead (two register sets); TR: pairs of transposing reads
-// pseudo-random bf16 in (-1, 1) from an integer (a multiplicative hash; no statistical claims)
-__device__ __forceinline__ bf16_t probe_noise(unsigned i) {
-  i = (i + 0x9e3779b9u) * 0x85ebca6bu;
-  i ^= i >> 15;
-  i *= 0xc2b2ae35u;
-  i ^= i >> 13;
-  return (bf16_t)((float)(int)(i >> 8) * (1.0f / 8388608.0f) - 1.0f);
-}
-
 template <int NW, int R, bool TR, bool NOISE = false>
 __global__ __launch_bounds__(NW * 64) void probe_feed_kernel(float* out, long long* cyc, int iters) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -268,6 +271,7 @@ int sustained(int variant, double* result, hipStream_t st) {
     case 0: return run_probe(probe_feed_kernel<NW, 0, false, true>, NW, 65536, false, 2.0, result, st, kSustainedLaunches);
     case 1: return run_probe(probe_feed_kernel<NW, 2, false, true>, NW, 65536, false, 2.0, result, st, kSustainedLaunches);
     case 2: return run_probe(probe_feed_kernel<NW, 3, false, true>, NW, 65536, false, 2.0, result, st, kSustainedLaunches);
+    case 3: return run_probe(probe_arrangement_kernel<NW, 0, true>, NW, 0, false, 1.0, result, st, kSustainedLaunches / 2);
   }
   return fail(-1, "probe: sustained variant %d", variant);
 }

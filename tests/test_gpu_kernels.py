@@ -530,7 +530,9 @@ def test_issue_rate_probe_reports_the_matrix_pipe_rate(K):
     assert 128.0 <= cycles < 160.0 and ms > 0.0 and 0.5 < ghz < 3.0, (cycles, ms, ghz)
     with pytest.raises(K.DLayerError):
         K.issue_rate_probe(4, 0, 2)
+    cycles, ms, ghz, _ = K.issue_rate_probe(3, 3, 2)      # 16 MFMAs 32x32x16 of 32 cycles each per block
+    assert 512.0 <= cycles < 560.0 and ms > 0.0 and 0.5 < ghz < 3.0, (cycles, ms, ghz)
     with pytest.raises(K.DLayerError):
-        K.issue_rate_probe(3, 3, 2)
+        K.issue_rate_probe(3, 4, 2)
     with pytest.raises(K.DLayerError):
         K.issue_rate_probe(0, 0, 3)
