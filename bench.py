@@ -27,7 +27,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published: 2.5 PFLOP/
 # run (factors 2.0 and 1.0; profiles/layer_8b_hbm_traffic.txt).  Only valid for the GEMM source the
 # counters were taken on: reported as null when gemm.hip has changed since.
 GEMM_TRAFFIC = {"config": "8b", "gemm_hip_sha256": "f94e8db7edcbef10e1afe77c4e421204cea0725d8f7e95c0786bbaca67d9b716",
-                "fetch_bytes": 1.497e+09, "write_bytes": 2.013e+08}
+                "fetch_bytes": 1.496e+09, "write_bytes": 2.013e+08}
 
 
 def _gemm_traffic(config_name):
