@@ -17,6 +17,8 @@
 // An MFMA sums over its 16 k-slots in any order, so the slot -> key assignment is chosen to match
 // the accumulator layout of the score tile: for a 16-key step, slot (half = lane / 32, e = 0..7)
 // holds key 8*(e/4) + 4*half + e%4.  The transposed loads of the other operand use the same map.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -54,6 +56,8 @@ struct RowTile {
   static constexpr int BYTES = ROWS * ROW_B;
 
   // rs describes memory starting at the tile's first row; ld = row stride in elements.
+  // AUX: cache-policy bits of the load (0 = default, 2 = non-temporal)
+  template <int AUX = 0>
   static __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, char* lds_tile, int wave,
                                                int lane, int64_t ld) {
     const int r = lane / LPR, pc = lane % LPR;
@@ -63,7 +67,7 @@ struct RowTile {
       const int c = pc ^ swz(i * RPI + r);   // rows per wave are a multiple of 16
       const uint32_t vo = (uint32_t)(r * ld * 2 + (c << 4));
       const uint32_t so = (uint32_t)((int64_t)j * RPI * ld * 2);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, vo, so, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(lds_tile + j * 1024), 16, vo, so, 0, AUX);
     }
   }
   // MFMA operand for rows row0 + lane%32, contraction over the DH index, step kk (16 of DH).
@@ -598,6 +602,157 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// dS handed from the dK/dV pass to the dQ pass (head dims 64 and 128), so that dQ is one product per tile
+// instead of three (S and dP are not formed a second time).  Storage, bf16, lower triangle only:
+//   per (batch, query head): query blocks qb of 128 rows, each followed by its 2 (qb + 1) key tiles of 64;
+//   one (query block, key tile) unit = 16 KiB = four sub-tiles of 4 KiB, one per 32 query rows of the block;
+//   a sub-tile is [64 keys][32 query slots], 64 bytes per key; slot p of a key holds query row
+//   16 ((p >> 3) & 1) + 8 ((p >> 2) & 1) + 4 (p >> 4) + (p & 3) of the 32 - the order in which a lane of the
+//   dK/dV kernel holds the packed dS operand, so it stores 2 x 16 bytes per tile and a wave 2 KiB in a run.
+// The dQ pass reads a unit as one contiguous 16 KiB tile per 64 keys.
+// ------------------------------------------------------------------------------------------
+struct DsLayout {
+  static constexpr int64_t UNIT = 16384, SUB = 4096;
+  static __host__ __device__ __forceinline__ int64_t block_unit(int64_t qb) { return qb * (qb + 1); }   // units before block qb
+  static __host__ __device__ __forceinline__ int64_t head_units(int64_t S) { return block_unit(S / 128); }
+  static __device__ __forceinline__ int slot_row(int p) { return (((p >> 3) & 1) << 4) | (((p >> 2) & 1) << 3) | ((p >> 4) << 2) | (p & 3); }
+};
+
+// dQ from the stored dS: workgroup = 128 query rows of one (batch, head), wave = 32 rows (one sub-tile per
+// key tile); dQ^T[d][q] += K^T[d][key] dS^T[key][q] with both operands read from row-major LDS tiles through
+// transposing reads.  Lane l of a wave owns query slot l % 32, i.e. row slot_row(l % 32) of the wave's 32.
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
+    const bf16_t* __restrict__ k, const bf16_t* __restrict__ ds, bf16_t* __restrict__ dq, int B, int S, int Hq,
+    int Hkv, float scale, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, int rope_layout) {
+  using KTile = RowTile<64, DH, 4>;
+  using DTile = RowTile<64, 32, 1>;
+  static_assert(DTile::BYTES == DsLayout::SUB && (DH == 64 || DH == 128), "sub-tile size, head dims with a dK/dV pass that stores dS");
+  // LDS: two stages of K tiles, then three of dS tiles (one 4 KiB sub-tile per wave): the dS tiles are the
+  // kernel's HBM stream and are requested two tiles ahead, the K tiles (L2 hits) one ahead
+  constexpr int KRING = 2 * KTile::BYTES, DSTAGE = 4 * DTile::BYTES;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int j, pair;
+  split_block_id((int)blockIdx.x, B * Hkv, j, pair);
+  const int G = Hq / Hkv, b = pair / Hkv, hk = pair % Hkv;
+  const int qb = S / 128 - 1 - j / G, h = hk * G + j % G;   // long rows (late query blocks) first
+  const int half = lane >> 5;
+  const int qrow = qb * 128 + wave * 32 + DsLayout::slot_row(lane & 31);
+  const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
+
+  f32x16 acc[DH / 32];
+#pragma unroll
+  for (int t = 0; t < DH / 32; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+
+  const bf16_t* kb = k + (int64_t)b * S * ldk + (int64_t)hk * DH;
+  const uint32_t kv_bytes = (uint32_t)((((int64_t)S - 1) * ldk + DH) * 2);
+  const char* dsb = reinterpret_cast<const char*>(ds) +
+                    (DsLayout::head_units(S) * ((int64_t)b * Hq + h) + DsLayout::block_unit(qb)) * DsLayout::UNIT + wave * DsLayout::SUB;
+  const int nkv = 2 * (qb + 1);
+  auto issue_k = [&](int t) {
+    const uint32_t skip = (uint32_t)((int64_t)t * 64 * ldk * 2);
+    KTile::issue(attn_rsrc(kb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + (t & 1) * KTile::BYTES, wave, lane, ldk);
+  };
+  auto issue_ds = [&](int t, int dstage) {
+    DTile::template issue<2>(attn_rsrc(dsb + (int64_t)t * DsLayout::UNIT, (uint32_t)DsLayout::SUB),
+                             smem + KRING + dstage * DSTAGE + wave * DTile::BYTES, 0, lane, 32);
+  };
+  // LDS addresses of the transposed reads for 16-key step 0 of stage 0 (see RowTile::frag_cols); later steps
+  // and the other stage are immediate offsets / one add away because the swizzle repeats every 16 rows.
+  constexpr int NT2 = DH / 32;
+  uint32_t ka[NT2][2], da[2];
+  {
+    const int grp = lane >> 4, sl = lane & 15, e = sl >> 2, g = sl & 3;
+    const int row = ((grp >> 1) << 2) + e, colq = ((grp & 1) << 4) + (g << 2);
+    const uint32_t s0 = (uint32_t)(uintptr_t)(LDS_PTR(char))smem;
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+      const int r = row + rr * 8;
+#pragma unroll
+      for (int t2 = 0; t2 < NT2; ++t2) {
+        const int col = t2 * 32 + colq;
+        ka[t2][rr] = s0 + r * KTile::ROW_B + ((((col >> 3) ^ KTile::swz(r)) << 4) | ((col & 7) << 1));
+      }
+      da[rr] = s0 + KRING + wave * DTile::BYTES + r * DTile::ROW_B + ((((colq >> 3) ^ DTile::swz(r)) << 4) | ((colq & 7) << 1));
+    }
+  }
+  issue_k(0);
+  issue_ds(0, 0);
+  issue_ds(1, 1);            // nkv >= 2
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  int dcur = 0;              // dS stage of tile t; tile t + 2 goes to the stage tile t - 1 used
+  for (int t = 0; t < nkv; ++t) {
+    // K of the next tile first, then dS two tiles ahead: the wait at the bottom leaves the latter in flight
+    if (t + 1 < nkv) issue_k(t + 1);
+    const bool ahead = t + 2 < nkv;
+    if (ahead) issue_ds(t + 2, dcur == 0 ? 2 : dcur - 1);
+    const uint32_t sbk = (uint32_t)((t & 1) * KTile::BYTES), sbd = (uint32_t)(dcur * DSTAGE);
+    // The reads are inline assembly (the compiler would put a wait for the tile loads just issued in front
+    // of the builtin, which it cannot tell apart from the stage being filled) and are neither counted nor
+    // moved by the compiler: fragments of step ks + 1 are requested before the products of step ks, and
+    // every use sits behind a wait that names the fragments.
+    bf16x8 kf[2][NT2], df[2];
+    auto request = [&](auto KS) {
+      constexpr int ks = decltype(KS)::value, bi = ks & 1;
+      bf16x4 lo, hi;
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(da[0] + sbd), "n"(ks * 16 * DTile::ROW_B));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(da[1] + sbd), "n"(ks * 16 * DTile::ROW_B));
+      df[bi].lo = lo; df[bi].hi = hi;
+#pragma unroll
+      for (int t2 = 0; t2 < NT2; ++t2) {
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(ka[t2][0] + sbk), "n"(ks * 16 * KTile::ROW_B));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(ka[t2][1] + sbk), "n"(ks * 16 * KTile::ROW_B));
+        kf[bi][t2].lo = lo; kf[bi][t2].hi = hi;
+      }
+    };
+    auto step = [&](auto KS) {
+      constexpr int ks = decltype(KS)::value, bi = ks & 1;
+      if constexpr (ks < 3) {
+        request(std::integral_constant<int, ks + 1>{});
+        if constexpr (NT2 == 4)
+          asm volatile("s_waitcnt lgkmcnt(10)" : "+v"(df[bi]), "+v"(kf[bi][0]), "+v"(kf[bi][1]), "+v"(kf[bi][2]), "+v"(kf[bi][3]));
+        else
+          asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(df[bi]), "+v"(kf[bi][0]), "+v"(kf[bi][1]));
+      } else {
+        if constexpr (NT2 == 4)
+          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(df[bi]), "+v"(kf[bi][0]), "+v"(kf[bi][1]), "+v"(kf[bi][2]), "+v"(kf[bi][3]));
+        else
+          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(df[bi]), "+v"(kf[bi][0]), "+v"(kf[bi][1]));
+      }
+#pragma unroll
+      for (int t2 = 0; t2 < NT2; ++t2)
+        acc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi][t2], df[bi], acc[t2], 0, 0, 0);
+    };
+    request(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 3>{});
+    static_assert(DTile::PER_WAVE == 4, "the wait below counts the dS loads of one tile");
+    if (ahead) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    dcur = dcur == 2 ? 0 : dcur + 1;
+  }
+  // q was rotated after its projection: hand back the gradient of the unrotated q
+  if (rope_cos) rope_unrotate<DH>(acc, rope_cos + (int64_t)qrow * (DH / 2), rope_sin + (int64_t)qrow * (DH / 2), rope_layout, half);
+  bf16_t* op = dq + ((int64_t)b * S + qrow) * ldq + (int64_t)h * DH + half * 4;
+#pragma unroll
+  for (int t2 = 0; t2 < DH / 32; ++t2)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 ov;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(acc[t2][g * 4 + e] * scale);
+      *reinterpret_cast<bf16x4*>(op + t2 * 32 + g * 8) = ov;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // dK and dV in one pass (head dims 64 and 128).  Workgroup = 4 waves = 128 keys of one (batch, kv head),
 // wave = 32 keys; it streams 32-row Q / dO tiles of every query head of the group from the last query
 // tile back to the diagonal.  Per tile: S = Q K^T and dP = dO V^T - delta once, P = exp2(..), dS = P dP,
@@ -606,12 +761,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 // To hold both accumulators at two waves per SIMD the wave's V fragments live in LDS (the 128-key V tile
 // stays resident), only its K fragments in registers, and the query tile is 32 rows.
 // ------------------------------------------------------------------------------------------
-template <int DH>
+template <int DH, bool WRITE_DS>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ d_o, const float* __restrict__ lse2, const float* __restrict__ delta,
-    bf16_t* __restrict__ dk_out, bf16_t* __restrict__ dv_out, int B, int S, int Hq, int Hkv, float scale,
-    const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, int rope_layout) {
+    bf16_t* __restrict__ dk_out, bf16_t* __restrict__ dv_out, bf16_t* __restrict__ ds_out, int B, int S, int Hq,
+    int Hkv, float scale, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, int rope_layout) {
   using VTile = RowTile<128, DH, 4>;
   using Tile = RowTile<32, DH, 1>;          // addressing of a 32-row tile; loaded by issue32 below
   constexpr int TB = 32 * DH * 2;           // one Q or dO tile
@@ -656,6 +811,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(
     }
   };
   int ld_g = 0, ld_qt = S / 32 - 1, cur_g = 0, cur_qt = S / 32 - 1;
+  const uint32_t ds_lane = (uint32_t)(lk * 64 + half * 32);
   auto issue_tile = [&](int stage) {
     const int h = hk * G + ld_g, qrow = ld_qt * 32;
     if (++ld_g == G) { ld_g = 0; --ld_qt; }
@@ -695,15 +851,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(
       asm volatile("" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]));
     if (it + 1 < niter) issue_tile(stage ^ 1);
     const int qrow = cur_qt * 32;
+    // where this wave's 32 keys x 32 queries of dS go (layout: DsLayout above)
+    const char* ds_dst = reinterpret_cast<const char*>(ds_out) +
+                         (DsLayout::head_units(S) * ((int64_t)b * Hq + hk * G + cur_g) + DsLayout::block_unit(cur_qt >> 2) + 2 * kt + (wave >> 1)) * DsLayout::UNIT +
+                         (cur_qt & 3) * DsLayout::SUB + (wave & 1) * 2048;   // wave-uniform; the lane adds ds_lane
     if (++cur_g == G) { cur_g = 0; --cur_qt; }
     const char* tq = smem + stage * STAGE;
     const char* tdo = tq + TB;
     const float* stat = reinterpret_cast<const float*>(tq + 2 * TB);
     // S[q][kv] and dP[q][kv] - delta[q] for the 32 queries: lane owns key kvw + lk, queries along registers
+    // (the lane's offset into the statistics is formed anew every iteration: kept across the loop it is the
+    // value the register allocator spills, and its reload would sit right behind the tile loads above)
+    int half_l = half;
+    asm volatile("" : "+v"(half_l));
     f32x16 s, dp;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 64 + g * 8 + half * 4);
+      const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 64 + g * 8 + half_l * 4);
 #pragma unroll
       for (int e = 0; e < 4; ++e) { s[g * 4 + e] = 0.f; dp[g * 4 + e] = d4[e]; }
     }
@@ -714,7 +878,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + g * 8 + half * 4);
+      const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + g * 8 + half_l * 4);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int r = g * 4 + e;
@@ -732,16 +896,25 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(
         if (((r >> 2) << 3) + (r & 3) < first_ok) { s[r] = 0.f; dp[r] = 0.f; }
     }
     // dV^T[d][kv] += dO^T[d][q] P[q][kv]   and   dK^T[d][kv] += Q^T[d][q] dS[q][kv]
+    const bf16x8 df0 = pack_slots(dp, 0), df1 = pack_slots(dp, 8);
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      const bf16x8 pf = pack_slots(s, ks * 8), df = pack_slots(dp, ks * 8);
+      const bf16x8 pf = pack_slots(s, ks * 8), df = ks ? df1 : df0;
 #pragma unroll
       for (int t2 = 0; t2 < DH / 32; ++t2) {
         acc_v[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tdo, t2 * 32, ks * 16, lane), pf, acc_v[t2], 0, 0, 0);
         acc_k[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(tq, t2 * 32, ks * 16, lane), df, acc_k[t2], 0, 0, 0);
       }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // dS for the dQ pass.  The two stores are the last vector-memory instructions of the iteration and the
+    // wait below leaves exactly them in flight (the counter retires in issue order, so every tile load
+    // issued before them has landed); their latency is then covered by the next iteration instead of
+    // being waited for here.
+    if constexpr (WRITE_DS)
+      asm volatile("global_store_dwordx4 %0, %1, %3 nt\n\tglobal_store_dwordx4 %0, %2, %3 offset:16 nt\n\ts_waitcnt vmcnt(2)"
+                   :: "v"(ds_lane), "v"(df0), "v"(df1), "s"(ds_dst) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     stage ^= 1;
   }
@@ -781,8 +954,17 @@ int launch_attention_fwd(const void* q, const void* k, const void* v, int64_t B,
   return fwd_dh<32>(q, k, v, B, S, Hq, Hkv, o, lse, st);
 }
 
-size_t attention_bwd_workspace(int64_t B, int64_t S, int64_t Hq, int64_t, int64_t) {
-  return 2 * (size_t)B * Hq * S * sizeof(float);   // -rowsum(dO * O) and lse * log2(e)
+// -rowsum(dO * O) and lse * log2(e), then (head dims 64 and 128) the dS tiles of DsLayout
+static size_t bwd_stats_bytes(int64_t B, int64_t S, int64_t Hq) {
+  return (2 * (size_t)B * Hq * S * sizeof(float) + 4095) / 4096 * 4096;
+}
+// Handing dS over costs its HBM round trip (2 bytes per causal score, written and read once) and saves two of
+// the dQ pass's three products: worth it once the sequences are long enough for the products to dominate
+// (measured: -6 % on the backward at S = 8192 and 2048 with 128-wide heads, +5 % at S = 1024 with 64-wide ones).
+static bool ds_handoff(int64_t S, int64_t dh) { return dh >= 64 && S >= 2048; }
+size_t attention_bwd_workspace(int64_t B, int64_t S, int64_t Hq, int64_t, int64_t dh) {
+  const size_t stats = bwd_stats_bytes(B, S, Hq);
+  return ds_handoff(S, dh) ? stats + (size_t)B * Hq * DsLayout::head_units(S) * DsLayout::UNIT : stats;
 }
 
 template <int DH>
@@ -798,17 +980,29 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
                      (const bf16_t*)o, (const bf16_t*)d_o, lse, delta, lse2, rows, (int)S, (int)Hq);
   if (int rc = check_launch("attention_backward(delta)")) return rc;
   const float scale = (float)(1.0 / sqrt((double)DH));
-  const size_t lds_dq = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
-  static std::atomic<unsigned long long> done_dq{0};
-  if (int rc = reserve_lds(attn_bwd_dq_kernel<DH>, lds_dq, done_dq, "attention_backward")) return rc;
-  const dim3 kv_grid((unsigned)(S / 128 * Hkv * B));
+  const dim3 kv_grid((unsigned)(S / 128 * Hkv * B)), q_grid((unsigned)(S / 128 * Hq * B));
   if constexpr (DH >= 64) {
     const size_t lds_m = 2 * (2 * (size_t)(32 * DH * 2) + 512) + (size_t)RowTile<128, DH, 4>::BYTES;
+    if (ds_handoff(S, DH)) {
+      bf16_t* ds = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(workspace) + bwd_stats_bytes(B, S, Hq));
+      static std::atomic<unsigned long long> done_m{0};
+      if (int rc = reserve_lds(attn_bwd_dkdv_kernel<DH, true>, lds_m, done_m, "attention_backward")) return rc;
+      hipLaunchKernelGGL((attn_bwd_dkdv_kernel<DH, true>), kv_grid, dim3(256), lds_m, st, (const bf16_t*)q, (const bf16_t*)k,
+                         (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (bf16_t*)dv, ds,
+                         (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+      if (int rc = check_launch("attention_backward(dk, dv)")) return rc;
+      const size_t lds_q = 2 * (size_t)RowTile<64, DH, 4>::BYTES + 3 * 4 * (size_t)RowTile<64, 32, 1>::BYTES;
+      static std::atomic<unsigned long long> done_q{0};
+      if (int rc = reserve_lds(attn_bwd_dq_from_ds_kernel<DH>, lds_q, done_q, "attention_backward")) return rc;
+      hipLaunchKernelGGL(attn_bwd_dq_from_ds_kernel<DH>, q_grid, dim3(256), lds_q, st, (const bf16_t*)k, (const bf16_t*)ds,
+                         (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+      return check_launch("attention_backward(dq)");
+    }
     static std::atomic<unsigned long long> done_m{0};
-    if (int rc = reserve_lds(attn_bwd_dkdv_kernel<DH>, lds_m, done_m, "attention_backward")) return rc;
-    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<DH>, kv_grid, dim3(256), lds_m, st, (const bf16_t*)q, (const bf16_t*)k,
+    if (int rc = reserve_lds(attn_bwd_dkdv_kernel<DH, false>, lds_m, done_m, "attention_backward")) return rc;
+    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<DH, false>), kv_grid, dim3(256), lds_m, st, (const bf16_t*)q, (const bf16_t*)k,
                        (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (bf16_t*)dv,
-                       (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+                       (bf16_t*)nullptr, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
     if (int rc = check_launch("attention_backward(dk, dv)")) return rc;
   } else {
     const size_t lds_kv = 2 * (2 * (size_t)RowTile<64, DH, 4>::BYTES + 512);
@@ -824,9 +1018,12 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
                        (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
     if (int rc = check_launch("attention_backward(dk)")) return rc;
   }
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, dim3((unsigned)(S / 128 * Hq * B)), dim3(256),
-                     lds_dq, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)d_o, lse,
-                     (const float*)delta, (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+  const size_t lds_dq = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
+  static std::atomic<unsigned long long> done_dq{0};
+  if (int rc = reserve_lds(attn_bwd_dq_kernel<DH>, lds_dq, done_dq, "attention_backward")) return rc;
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, q_grid, dim3(256), lds_dq, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                     (const bf16_t*)d_o, lse, (const float*)delta, (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos,
+                     rope_sin, rope_layout);
   return check_launch("attention_backward(dq)");
 }
 

@@ -299,7 +299,9 @@ def test_linear_full_size_sampled(K, Kd, N, res):
 # other cases the plain one
 ATTN_CASES = [(2, 128, 4, 4, 32, 1.0), (1, 384, 4, 2, 64, 1.0), (2, 256, 8, 2, 128, 1.0),
               (1, 512, 4, 1, 128, 4.0), (1, 1024, 2, 2, 64, 1.0), (2, 512, 8, 4, 128, 1.0),
-              (4, 384, 8, 4, 64, 1.0)]
+              (4, 384, 8, 4, 64, 1.0),
+              # from 2048 positions on the dK/dV pass hands dS to the dQ pass through the workspace
+              (1, 2048, 4, 2, 64, 1.0), (2, 2048, 4, 1, 128, 1.0), (1, 2304, 2, 2, 128, 1.0)]
 
 
 @pytest.mark.parametrize("B,S,Hq,Hkv,dh,qk_std", ATTN_CASES)
@@ -326,7 +328,11 @@ def test_attention_forward_backward(K, B, S, Hq, Hkv, dh, qk_std):
     # gradients: the acceptance bar is the cosine; the element-wise bound is looser than for
     # outputs because P and dS are rounded to bf16 before their second product, and with
     # near-one-hot softmax rows (qk_std 4) dS = P (dP - delta) is a difference of nearly equal terms
-    gtol = 5e-2 if qk_std == 1.0 else np.inf
+    # From 2048 positions on the bound is the one of the full-size test below, for its reason: the metric
+    # scales by the rms of the reference, which the long late rows pull down, while the rounding error of
+    # the early rows does not shrink (6.0e-2 and 6.8e-2 on the two 128-wide cases, with or without the dS
+    # hand-over: both routes give the same bits).
+    gtol = np.inf if qk_std != 1.0 else (5e-2 if S < 2048 else 1e-1)
     assert_close(dq, dq_ref, "dq", rel_tol=gtol)
     assert_close(dk, dk_ref, "dk", rel_tol=gtol)
     assert_close(dv, dv_ref, "dv", rel_tol=gtol)
