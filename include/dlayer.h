@@ -254,7 +254,10 @@ int attention_forward(const void* q, const void* k, const void* v, int64_t batch
 /* Gradient of attention_forward: with P = exp(s - lse), dP = dO V^T, delta = rowsum(dO * O),
  * dS = P * (dP - delta):  dV_j = sum_h P_h^T dO_h, dQ_h = dS_h K_j / sqrt(dh),
  * dK_j = sum_h dS_h^T Q_h / sqrt(dh), sums over the query heads h of KV group j.
- * workspace: attention_backward_workspace_bytes(...).                                       */
+ * workspace (device): attention_backward_workspace_bytes(...) - two f32 per (head, position)
+ * and, for head_dim >= 64 and seq >= 2048, the causal half of dS in bf16 (seq * (seq + 128)
+ * bytes per (batch, query head): 4.4 GB at batch 2, seq 8192, 32 heads), which the dK/dV
+ * pass writes and the dQ pass reads back instead of forming S and dP a second time.        */
 size_t attention_backward_workspace_bytes(int64_t batch, int64_t seq, int64_t n_q_heads,
                                           int64_t n_kv_heads, int64_t head_dim);
 int attention_backward(const void* q, const void* k, const void* v, const void* o,
