@@ -338,6 +338,32 @@ def test_attention_forward_backward(K, B, S, Hq, Hkv, dh, qk_std):
     assert_close(dv, dv_ref, "dv", rel_tol=gtol)
 
 
+def test_attention_backward_with_ds_handover_is_reproducible_and_ignores_stale_workspace(K):
+    """From 2048 positions on the dK/dV pass stores dS in the workspace and the dQ pass reads it back: every
+    tile read must have been written by the same call (a workspace full of NaN or of another call's leftovers
+    changes nothing), and two runs agree bit for bit."""
+    B, S, Hq, Hkv, dh = 2, 2048, 8, 2, 128
+    rng = np.random.default_rng(11)
+    qd, kd = dev_bf16(_rand_bits(rng, (B, S, Hq, dh))), dev_bf16(_rand_bits(rng, (B, S, Hkv, dh)))
+    vd, dod = dev_bf16(_rand_bits(rng, (B, S, Hkv, dh))), dev_bf16(_rand_bits(rng, (B, S, Hq, dh)))
+    o = torch.empty_like(qd)
+    lse = torch.empty(B, Hq, S, dtype=torch.float32, device="cuda")
+    K.attention_forward(qd, kd, vd, B, S, Hq, Hkv, dh, o, lse)
+    nbytes = K.attention_backward_workspace_bytes(B, S, Hq, Hkv, dh)
+    assert nbytes >= B * Hq * S * (S + 128)          # the causal half of dS, 2 bytes per score
+    outs = []
+    for fill in (0xFF, 0x3C, None):                  # NaN patterns, bf16 ones, then the previous call's contents
+        ws = torch.full((nbytes,), fill, dtype=torch.uint8, device="cuda") if fill is not None else ws
+        dq, dk, dv = torch.full_like(qd, float("nan")), torch.full_like(kd, float("nan")), torch.full_like(vd, float("nan"))
+        K.attention_backward(qd, kd, vd, o, dod, lse, B, S, Hq, Hkv, dh, dq, dk, dv, ws)
+        torch.cuda.synchronize()
+        assert not torch.isnan(dq.float()).any()
+        outs.append((dq, dk, dv))
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
 def test_attention_full_size_one_group(K):
     """The attention of the 8B-shaped layer at full size (B2 S8192 32q/8kv x128), in the launch
     configuration the benchmark times.  One (batch row, kv head) group is a closed sub-problem: its
