@@ -255,7 +255,7 @@ int attention_forward(const void* q, const void* k, const void* v, int64_t batch
  * dS = P * (dP - delta):  dV_j = sum_h P_h^T dO_h, dQ_h = dS_h K_j / sqrt(dh),
  * dK_j = sum_h dS_h^T Q_h / sqrt(dh), sums over the query heads h of KV group j.
  * workspace (device): attention_backward_workspace_bytes(...) - two f32 per (head, position)
- * and, for head_dim >= 64 and seq >= 2048, the causal half of dS in bf16 (seq * (seq + 128)
+ * and, for head_dim 128 and seq >= 2048, the causal half of dS in bf16 (seq * (seq + 128)
  * bytes per (batch, query head): 4.4 GB at batch 2, seq 8192, 32 heads), which the dK/dV
  * pass writes and the dQ pass reads back instead of forming S and dP a second time.        */
 size_t attention_backward_workspace_bytes(int64_t batch, int64_t seq, int64_t n_q_heads,

@@ -602,7 +602,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// dS handed from the dK/dV pass to the dQ pass (head dims 64 and 128), so that dQ is one product per tile
+// dS handed from the dK/dV pass to the dQ pass (128-wide heads, long sequences), so that dQ is one product per tile
 // instead of three (S and dP are not formed a second time).  Storage, bf16, lower triangle only:
 //   per (batch, query head): query blocks qb of 128 rows, each followed by its 2 (qb + 1) key tiles of 64;
 //   one (query block, key tile) unit = 16 KiB = four sub-tiles of 4 KiB, one per 32 query rows of the block;
@@ -627,7 +627,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
     int Hkv, float scale, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, int rope_layout) {
   using KTile = RowTile<64, DH, 4>;
   using DTile = RowTile<64, 32, 1>;
-  static_assert(DTile::BYTES == DsLayout::SUB && (DH == 64 || DH == 128), "sub-tile size, head dims with a dK/dV pass that stores dS");
+  static_assert(DTile::BYTES == DsLayout::SUB, "sub-tile size");
   // LDS: two stages of K tiles, then three of dS tiles (one 4 KiB sub-tile per wave): the dS tiles are the
   // kernel's HBM stream and are requested two tiles ahead, the K tiles (L2 hits) one ahead
   constexpr int KRING = 2 * KTile::BYTES, DSTAGE = 4 * DTile::BYTES;
@@ -959,9 +959,10 @@ static size_t bwd_stats_bytes(int64_t B, int64_t S, int64_t Hq) {
   return (2 * (size_t)B * Hq * S * sizeof(float) + 4095) / 4096 * 4096;
 }
 // Handing dS over costs its HBM round trip (2 bytes per causal score, written and read once) and saves two of
-// the dQ pass's three products: worth it once the sequences are long enough for the products to dominate
-// (measured: -6 % on the backward at S = 8192 and 2048 with 128-wide heads, +5 % at S = 1024 with 64-wide ones).
-static bool ds_handoff(int64_t S, int64_t dh) { return dh >= 64 && S >= 2048; }
+// the dQ pass's three products, whose cost grows with the head dim: worth it for 128-wide heads once the
+// sequences are long enough for the products to dominate (measured on the backward: -6 % at S = 2048 to
+// 16384 with 128-wide heads; with 64-wide heads +4 % at S = 2048, +11 % at 4096 and +29 % at 8192).
+static bool ds_handoff(int64_t S, int64_t dh) { return dh == 128 && S >= 2048; }
 size_t attention_bwd_workspace(int64_t B, int64_t S, int64_t Hq, int64_t, int64_t dh) {
   const size_t stats = bwd_stats_bytes(B, S, Hq);
   return ds_handoff(S, dh) ? stats + (size_t)B * Hq * DsLayout::head_units(S) * DsLayout::UNIT : stats;
@@ -983,20 +984,22 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
   const dim3 kv_grid((unsigned)(S / 128 * Hkv * B)), q_grid((unsigned)(S / 128 * Hq * B));
   if constexpr (DH >= 64) {
     const size_t lds_m = 2 * (2 * (size_t)(32 * DH * 2) + 512) + (size_t)RowTile<128, DH, 4>::BYTES;
-    if (ds_handoff(S, DH)) {
-      bf16_t* ds = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(workspace) + bwd_stats_bytes(B, S, Hq));
-      static std::atomic<unsigned long long> done_m{0};
-      if (int rc = reserve_lds(attn_bwd_dkdv_kernel<DH, true>, lds_m, done_m, "attention_backward")) return rc;
-      hipLaunchKernelGGL((attn_bwd_dkdv_kernel<DH, true>), kv_grid, dim3(256), lds_m, st, (const bf16_t*)q, (const bf16_t*)k,
-                         (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (bf16_t*)dv, ds,
-                         (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
-      if (int rc = check_launch("attention_backward(dk, dv)")) return rc;
-      const size_t lds_q = 2 * (size_t)RowTile<64, DH, 4>::BYTES + 3 * 4 * (size_t)RowTile<64, 32, 1>::BYTES;
-      static std::atomic<unsigned long long> done_q{0};
-      if (int rc = reserve_lds(attn_bwd_dq_from_ds_kernel<DH>, lds_q, done_q, "attention_backward")) return rc;
-      hipLaunchKernelGGL(attn_bwd_dq_from_ds_kernel<DH>, q_grid, dim3(256), lds_q, st, (const bf16_t*)k, (const bf16_t*)ds,
-                         (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
-      return check_launch("attention_backward(dq)");
+    if constexpr (DH == 128) {
+      if (ds_handoff(S, DH)) {
+        bf16_t* ds = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(workspace) + bwd_stats_bytes(B, S, Hq));
+        static std::atomic<unsigned long long> done_m{0};
+        if (int rc = reserve_lds(attn_bwd_dkdv_kernel<DH, true>, lds_m, done_m, "attention_backward")) return rc;
+        hipLaunchKernelGGL((attn_bwd_dkdv_kernel<DH, true>), kv_grid, dim3(256), lds_m, st, (const bf16_t*)q, (const bf16_t*)k,
+                           (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (bf16_t*)dv, ds,
+                           (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+        if (int rc = check_launch("attention_backward(dk, dv)")) return rc;
+        const size_t lds_q = 2 * (size_t)RowTile<64, DH, 4>::BYTES + 3 * 4 * (size_t)RowTile<64, 32, 1>::BYTES;
+        static std::atomic<unsigned long long> done_q{0};
+        if (int rc = reserve_lds(attn_bwd_dq_from_ds_kernel<DH>, lds_q, done_q, "attention_backward")) return rc;
+        hipLaunchKernelGGL(attn_bwd_dq_from_ds_kernel<DH>, q_grid, dim3(256), lds_q, st, (const bf16_t*)k, (const bf16_t*)ds,
+                           (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+        return check_launch("attention_backward(dq)");
+      }
     }
     static std::atomic<unsigned long long> done_m{0};
     if (int rc = reserve_lds(attn_bwd_dkdv_kernel<DH, false>, lds_m, done_m, "attention_backward")) return rc;

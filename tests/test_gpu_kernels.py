@@ -300,7 +300,8 @@ def test_linear_full_size_sampled(K, Kd, N, res):
 ATTN_CASES = [(2, 128, 4, 4, 32, 1.0), (1, 384, 4, 2, 64, 1.0), (2, 256, 8, 2, 128, 1.0),
               (1, 512, 4, 1, 128, 4.0), (1, 1024, 2, 2, 64, 1.0), (2, 512, 8, 4, 128, 1.0),
               (4, 384, 8, 4, 64, 1.0),
-              # from 2048 positions on the dK/dV pass hands dS to the dQ pass through the workspace
+              # from 2048 positions on, with 128-wide heads, the dK/dV pass hands dS to the dQ pass through the
+              # workspace (64-wide heads keep the three-product dQ kernel)
               (1, 2048, 4, 2, 64, 1.0), (2, 2048, 4, 1, 128, 1.0), (1, 2304, 2, 2, 128, 1.0)]
 
 
