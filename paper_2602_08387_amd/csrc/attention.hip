@@ -606,16 +606,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 // instead of three (S and dP are not formed a second time).  Storage, bf16, lower triangle only:
 //   per (batch, query head): query blocks qb of 128 rows, each followed by its 2 (qb + 1) key tiles of 64;
 //   one (query block, key tile) unit = 16 KiB = four sub-tiles of 4 KiB, one per 32 query rows of the block;
-//   a sub-tile is [64 keys][32 query slots], 64 bytes per key; slot p of a key holds query row
-//   16 ((p >> 3) & 1) + 8 ((p >> 2) & 1) + 4 (p >> 4) + (p & 3) of the 32 - the order in which a lane of the
-//   dK/dV kernel holds the packed dS operand, so it stores 2 x 16 bytes per tile and a wave 2 KiB in a run.
+//   a sub-tile is [2 runs of 32 keys][2 planes][32 keys][16 query slots], 32 bytes per key and plane; slot
+//   p = 16 plane + c holds query row 16 plane + 8 ((c >> 2) & 1) + 4 (c >> 3) + (c & 3) of the 32 - plane and c
+//   are the 16-key step and the position (lane half, element) at which a lane of the dK/dV kernel holds the
+//   packed dS operand, so each of its two 16-byte stores covers 1 KiB without gaps over the wave.
 // The dQ pass reads a unit as one contiguous 16 KiB tile per 64 keys.
 // ------------------------------------------------------------------------------------------
 struct DsLayout {
   static constexpr int64_t UNIT = 16384, SUB = 4096;
   static __host__ __device__ __forceinline__ int64_t block_unit(int64_t qb) { return qb * (qb + 1); }   // units before block qb
   static __host__ __device__ __forceinline__ int64_t head_units(int64_t S) { return block_unit(S / 128); }
-  static __device__ __forceinline__ int slot_row(int p) { return (((p >> 3) & 1) << 4) | (((p >> 2) & 1) << 3) | ((p >> 4) << 2) | (p & 3); }
+  static __device__ __forceinline__ int slot_row(int p) { return (p & 16) | (((p >> 2) & 1) << 3) | (((p >> 3) & 1) << 2) | (p & 3); }
 };
 
 // dQ from the stored dS: workgroup = 128 query rows of one (batch, head), wave = 32 rows (one sub-tile per
@@ -626,11 +627,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ ds, bf16_t* __restrict__ dq, int B, int S, int Hq,
     int Hkv, float scale, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, int rope_layout) {
   using KTile = RowTile<64, DH, 4>;
-  using DTile = RowTile<64, 32, 1>;
-  static_assert(DTile::BYTES == DsLayout::SUB, "sub-tile size");
+  constexpr int DSUB = (int)DsLayout::SUB;
   // LDS: two stages of K tiles, then three of dS tiles (one 4 KiB sub-tile per wave): the dS tiles are the
   // kernel's HBM stream and are requested two tiles ahead, the K tiles (L2 hits) one ahead
-  constexpr int KRING = 2 * KTile::BYTES, DSTAGE = 4 * DTile::BYTES;
+  constexpr int KRING = 2 * KTile::BYTES, DSTAGE = 4 * DSUB;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int j, pair;
@@ -657,8 +657,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
     KTile::issue(attn_rsrc(kb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + (t & 1) * KTile::BYTES, wave, lane, ldk);
   };
   auto issue_ds = [&](int t, int dstage) {
-    DTile::template issue<2>(attn_rsrc(dsb + (int64_t)t * DsLayout::UNIT, (uint32_t)DsLayout::SUB),
-                             smem + KRING + dstage * DSTAGE + wave * DTile::BYTES, 0, lane, 32);
+    // the wave's sub-tile as it is stored: four wave-wide 1 KiB loads, non-temporal (read once)
+    const __amdgpu_buffer_rsrc_t rs = attn_rsrc(dsb + (int64_t)t * DsLayout::UNIT, (uint32_t)DsLayout::SUB);
+    char* dst = smem + KRING + dstage * DSTAGE + wave * DSUB;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (LDS_PTR(void))(dst + i * 1024), 16, (uint32_t)lane * 16, i * 1024, 0, 2);
   };
   // LDS addresses of the transposed reads for 16-key step 0 of stage 0 (see RowTile::frag_cols); later steps
   // and the other stage are immediate offsets / one add away because the swizzle repeats every 16 rows.
@@ -676,7 +680,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
         const int col = t2 * 32 + colq;
         ka[t2][rr] = s0 + r * KTile::ROW_B + ((((col >> 3) ^ KTile::swz(r)) << 4) | ((col & 7) << 1));
       }
-      da[rr] = s0 + KRING + wave * DTile::BYTES + r * DTile::ROW_B + ((((colq >> 3) ^ DTile::swz(r)) << 4) | ((colq & 7) << 1));
+      // dS: plane = the lane's 16-column half, 32-byte rows: the 16 lanes of a transposing read fetch 128
+      // contiguous bytes, so the stored layout needs no swizzle
+      da[rr] = s0 + KRING + wave * DSUB + (grp & 1) * 1024 + r * 32 + (g << 3);
     }
   }
   issue_k(0);
@@ -699,8 +705,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
     auto request = [&](auto KS) {
       constexpr int ks = decltype(KS)::value, bi = ks & 1;
       bf16x4 lo, hi;
-      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(da[0] + sbd), "n"(ks * 16 * DTile::ROW_B));
-      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(da[1] + sbd), "n"(ks * 16 * DTile::ROW_B));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(da[0] + sbd), "n"((ks >> 1) * 2048 + (ks & 1) * 512));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(da[1] + sbd), "n"((ks >> 1) * 2048 + (ks & 1) * 512));
       df[bi].lo = lo; df[bi].hi = hi;
 #pragma unroll
       for (int t2 = 0; t2 < NT2; ++t2) {
@@ -732,7 +738,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
     step(std::integral_constant<int, 1>{});
     step(std::integral_constant<int, 2>{});
     step(std::integral_constant<int, 3>{});
-    static_assert(DTile::PER_WAVE == 4, "the wait below counts the dS loads of one tile");
+    // four dS loads per wave and tile: the wait leaves those of tile t + 2 in flight
     if (ahead) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -811,7 +817,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(
     }
   };
   int ld_g = 0, ld_qt = S / 32 - 1, cur_g = 0, cur_qt = S / 32 - 1;
-  const uint32_t ds_lane = (uint32_t)(lk * 64 + half * 32);
+  const uint32_t ds_lane = (uint32_t)(lk * 32 + half * 16);
   auto issue_tile = [&](int stage) {
     const int h = hk * G + ld_g, qrow = ld_qt * 32;
     if (++ld_g == G) { ld_g = 0; --ld_qt; }
@@ -911,7 +917,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkdv_kernel(
     // issued before them has landed); their latency is then covered by the next iteration instead of
     // being waited for here.
     if constexpr (WRITE_DS)
-      asm volatile("global_store_dwordx4 %0, %1, %3 nt\n\tglobal_store_dwordx4 %0, %2, %3 offset:16 nt\n\ts_waitcnt vmcnt(2)"
+      asm volatile("global_store_dwordx4 %0, %1, %3 nt\n\tglobal_store_dwordx4 %0, %2, %3 offset:1024 nt\n\ts_waitcnt vmcnt(2)"
                    :: "v"(ds_lane), "v"(df0), "v"(df1), "s"(ds_dst) : "memory");
     else
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
