@@ -619,26 +619,29 @@ struct DsLayout {
   static __device__ __forceinline__ int slot_row(int p) { return (p & 16) | (((p >> 2) & 1) << 3) | (((p >> 3) & 1) << 2) | (p & 3); }
 };
 
-// dQ from the stored dS: workgroup = 128 query rows of one (batch, head), wave = 32 rows (one sub-tile per
-// key tile); dQ^T[d][q] += K^T[d][key] dS^T[key][q] with both operands read from row-major LDS tiles through
-// transposing reads.  Lane l of a wave owns query slot l % 32, i.e. row slot_row(l % 32) of the wave's 32.
-template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
+// dQ from the stored dS: workgroup = 128 query rows of NH query heads of one KV group (they share the K
+// tiles, which the first four waves load), wave = 32 rows of one head (one sub-tile per key tile);
+// dQ^T[d][q] += K^T[d][key] dS^T[key][q] with both operands read from LDS tiles through transposing reads.
+// Lane l of a wave owns query slot l % 32, i.e. row slot_row(l % 32) of the wave's 32.
+template <int DH, int NH>
+__global__ __launch_bounds__(256 * NH, 2 / NH) void attn_bwd_dq_from_ds_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ ds, bf16_t* __restrict__ dq, int B, int S, int Hq,
     int Hkv, float scale, const float* __restrict__ rope_cos, const float* __restrict__ rope_sin, int rope_layout) {
   using KTile = RowTile<64, DH, 4>;
   constexpr int DSUB = (int)DsLayout::SUB;
   // LDS: two stages of K tiles, then three of dS tiles (one 4 KiB sub-tile per wave): the dS tiles are the
   // kernel's HBM stream and are requested two tiles ahead, the K tiles (L2 hits) one ahead
-  constexpr int KRING = 2 * KTile::BYTES, DSTAGE = 4 * DSUB;
+  static_assert(NH == 1 || NH == 2, "one or two heads per workgroup");
+  constexpr int KRING = 2 * KTile::BYTES, DSTAGE = 4 * NH * DSUB;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int sub = wave & 3, hsel = wave >> 2;
   int j, pair;
   split_block_id((int)blockIdx.x, B * Hkv, j, pair);
-  const int G = Hq / Hkv, b = pair / Hkv, hk = pair % Hkv;
-  const int qb = S / 128 - 1 - j / G, h = hk * G + j % G;   // long rows (late query blocks) first
+  const int G = Hq / Hkv, GW = G / NH, b = pair / Hkv, hk = pair % Hkv;
+  const int qb = S / 128 - 1 - j / GW, h = hk * G + (j % GW) * NH + hsel;   // long rows (late query blocks) first
   const int half = lane >> 5;
-  const int qrow = qb * 128 + wave * 32 + DsLayout::slot_row(lane & 31);
+  const int qrow = qb * 128 + sub * 32 + DsLayout::slot_row(lane & 31);
   const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
 
   f32x16 acc[DH / 32];
@@ -650,11 +653,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
   const bf16_t* kb = k + (int64_t)b * S * ldk + (int64_t)hk * DH;
   const uint32_t kv_bytes = (uint32_t)((((int64_t)S - 1) * ldk + DH) * 2);
   const char* dsb = reinterpret_cast<const char*>(ds) +
-                    (DsLayout::head_units(S) * ((int64_t)b * Hq + h) + DsLayout::block_unit(qb)) * DsLayout::UNIT + wave * DsLayout::SUB;
+                    (DsLayout::head_units(S) * ((int64_t)b * Hq + h) + DsLayout::block_unit(qb)) * DsLayout::UNIT + sub * DsLayout::SUB;
   const int nkv = 2 * (qb + 1);
   auto issue_k = [&](int t) {
+    if (NH > 1 && hsel != 0) return;
     const uint32_t skip = (uint32_t)((int64_t)t * 64 * ldk * 2);
-    KTile::issue(attn_rsrc(kb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + (t & 1) * KTile::BYTES, wave, lane, ldk);
+    KTile::issue(attn_rsrc(kb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + (t & 1) * KTile::BYTES, sub, lane, ldk);
   };
   auto issue_ds = [&](int t, int dstage) {
     // the wave's sub-tile as it is stored: four wave-wide 1 KiB loads, non-temporal (read once)
@@ -738,7 +742,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_from_ds_kernel(
     step(std::integral_constant<int, 1>{});
     step(std::integral_constant<int, 2>{});
     step(std::integral_constant<int, 3>{});
-    // four dS loads per wave and tile: the wait leaves those of tile t + 2 in flight
+    // four dS loads per wave and tile, issued after the K loads: the wait leaves those of tile t + 2 in flight
     if (ahead) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -999,11 +1003,20 @@ static int bwd_dh(const void* q, const void* k, const void* v, const void* o, co
                            (const bf16_t*)v, (const bf16_t*)d_o, (const float*)lse2, (const float*)delta, (bf16_t*)dk, (bf16_t*)dv, ds,
                            (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
         if (int rc = check_launch("attention_backward(dk, dv)")) return rc;
-        const size_t lds_q = 2 * (size_t)RowTile<64, DH, 4>::BYTES + 3 * 4 * (size_t)RowTile<64, 32, 1>::BYTES;
-        static std::atomic<unsigned long long> done_q{0};
-        if (int rc = reserve_lds(attn_bwd_dq_from_ds_kernel<DH>, lds_q, done_q, "attention_backward")) return rc;
-        hipLaunchKernelGGL(attn_bwd_dq_from_ds_kernel<DH>, q_grid, dim3(256), lds_q, st, (const bf16_t*)k, (const bf16_t*)ds,
-                           (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+        // two query heads of a KV group per workgroup where the group has an even number of them
+        if ((Hq / Hkv) % 2 == 0) {
+          const size_t lds_q = 2 * (size_t)RowTile<64, DH, 4>::BYTES + 3 * 8 * (size_t)DsLayout::SUB;
+          static std::atomic<unsigned long long> done_q{0};
+          if (int rc = reserve_lds(attn_bwd_dq_from_ds_kernel<DH, 2>, lds_q, done_q, "attention_backward")) return rc;
+          hipLaunchKernelGGL((attn_bwd_dq_from_ds_kernel<DH, 2>), dim3(q_grid.x / 2), dim3(512), lds_q, st, (const bf16_t*)k,
+                             (const bf16_t*)ds, (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+        } else {
+          const size_t lds_q = 2 * (size_t)RowTile<64, DH, 4>::BYTES + 3 * 4 * (size_t)DsLayout::SUB;
+          static std::atomic<unsigned long long> done_q{0};
+          if (int rc = reserve_lds(attn_bwd_dq_from_ds_kernel<DH, 1>, lds_q, done_q, "attention_backward")) return rc;
+          hipLaunchKernelGGL((attn_bwd_dq_from_ds_kernel<DH, 1>), q_grid, dim3(256), lds_q, st, (const bf16_t*)k,
+                             (const bf16_t*)ds, (bf16_t*)dq, (int)B, (int)S, (int)Hq, (int)Hkv, scale, rope_cos, rope_sin, rope_layout);
+        }
         return check_launch("attention_backward(dq)");
       }
     }
