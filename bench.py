@@ -172,7 +172,7 @@ def time_components(torch, K, si, cfg, x, w, reps):
          lambda: K.linear_backward(h, w["w_gate"], dg, T, D, F, dx, None, 0, ws_lin)),
         ("o input gradient (+ W_o transpose)", "gemm_kernel<k,k>", 2.0 * T * QD * D,
          lambda: K.linear_backward(o, w["wo"], x, T, QD, D, dq, None, 0, ws_lin)),
-        ("attention backward (delta, dK+dV, dQ)", "attn_delta + attn_bwd_dkdv + attn_bwd_dq", 2.0 * attn,
+        ("attention backward (delta, dK+dV, dQ)", "attn_delta + attn_bwd_dkdv (stores dS) + attn_bwd_dq_from_ds", 2.0 * attn,
          lambda: K.attention_backward(q, k, v, o, dq, lse, B, S, Hq, Hkv, dh, dq, dk, dv, ws_attn)),
         ("seven weight gradients, one launch", "gemm_group_kernel<mn,mn>", sum(2.0 * T * N * Kd for _, _, _, N, Kd in wg),
          lambda: K.linear_wgrad_group([d for _, d, _, _, _ in wg], [xx for _, _, xx, _, _ in wg], [N for *_, N, _ in wg],
