@@ -151,17 +151,15 @@ __device__ __forceinline__ void split_block_id(int id, int npairs, int& j, int& 
 }
 
 // ------------------------------------------------------------------------------------------
-// Forward.  Workgroup = 128 query rows of NH query heads of one KV group, 4 waves per head, wave = 32 rows
-// of one head.  With NH = 2 the two heads share the K/V tiles, which the first four waves load (half the
-// L2 -> LDS traffic per product; measured -1.6 % at S = 8192, -4.7 % at S = 2048 with 128-wide heads).
+// Forward.  Workgroup = 4 waves = 128 query rows of one (batch, query head); wave = 32 rows.
 // The softmax is VALU-bound next to the MFMA work, so the per-tile VALU count is kept minimal:
 // the 1/sqrt(dh)*log2(e) scale is folded into the exp2 argument with one FMA, the causal mask runs
 // only on diagonal tiles, and the running maximum is only raised (and O and the row sum rescaled)
 // when some row's maximum grew by more than 2^8 - P then stays below 256, well inside bf16, and
 // the final O / rowsum is unchanged because both carry the same stale reference.
 // ------------------------------------------------------------------------------------------
-template <int DH, int NH>
-__global__ __launch_bounds__(256 * NH, 2 / NH) void attn_fwd_kernel(const bf16_t* __restrict__ q,
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ q,
                                                           const bf16_t* __restrict__ k,
                                                           const bf16_t* __restrict__ v,
                                                           bf16_t* __restrict__ o, float* __restrict__ lse,
@@ -172,10 +170,9 @@ __global__ __launch_bounds__(256 * NH, 2 / NH) void attn_fwd_kernel(const bf16_t
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int j, pair;
   split_block_id((int)blockIdx.x, B * Hkv, j, pair);
-  const int G = Hq / Hkv, GW = G / NH, b = pair / Hkv, hk = pair % Hkv;
-  const int sub = wave & 3, hsel = wave >> 2;
-  const int qt = S / 128 - 1 - j / GW, h = hk * G + (j % GW) * NH + hsel;   // long rows (late query tiles) first
-  const int q0 = qt * 128, qw = q0 + sub * 32;
+  const int G = Hq / Hkv, b = pair / Hkv, hk = pair % Hkv;
+  const int qt = S / 128 - 1 - j / G, h = hk * G + j % G;   // long rows (late query tiles) first
+  const int q0 = qt * 128, qw = q0 + wave * 32;
   const int lq = lane & 31, half = lane >> 5;
   const int64_t ldq = (int64_t)Hq * DH, ldk = (int64_t)Hkv * DH;
 
@@ -199,10 +196,9 @@ __global__ __launch_bounds__(256 * NH, 2 / NH) void attn_fwd_kernel(const bf16_t
   // One buffer descriptor per tile: base at the tile's first key row, range to the end of this
   // batch row's keys (rows past it would read as zero).
   auto issue_tile = [&](int t, int stage) {
-    if (NH > 1 && hsel != 0) return;
     const uint32_t skip = (uint32_t)((int64_t)t * 64 * ldk * 2);
-    Tile::issue(attn_rsrc(kb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + stage * STAGE, sub, lane, ldk);
-    Tile::issue(attn_rsrc(vb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + stage * STAGE + Tile::BYTES, sub, lane, ldk);
+    Tile::issue(attn_rsrc(kb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + stage * STAGE, wave, lane, ldk);
+    Tile::issue(attn_rsrc(vb + (int64_t)t * 64 * ldk, kv_bytes - skip), smem + stage * STAGE + Tile::BYTES, wave, lane, ldk);
   };
 
   issue_tile(0, 0);
@@ -952,19 +948,10 @@ template <int DH>
 static int fwd_dh(const void* q, const void* k, const void* v, int64_t B, int64_t S, int64_t Hq,
                   int64_t Hkv, void* o, float* lse, hipStream_t st) {
   const size_t lds = 2 * 2 * (size_t)RowTile<64, DH, 4>::BYTES;
-  const float scale_log2 = (float)(1.0 / sqrt((double)DH)) * kLog2e;
-  if constexpr (DH == 128) {
-    if ((Hq / Hkv) % 2 == 0) {   // two query heads of a KV group per workgroup
-      static std::atomic<unsigned long long> lds_done2{0};
-      if (int rc = reserve_lds(attn_fwd_kernel<DH, 2>, lds, lds_done2, "attention_forward")) return rc;
-      hipLaunchKernelGGL((attn_fwd_kernel<DH, 2>), dim3((unsigned)(S / 128 * Hq * B / 2)), dim3(512), lds, st, (const bf16_t*)q,
-                         (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse, (int)B, (int)S, (int)Hq, (int)Hkv, scale_log2);
-      return check_launch("attention_forward");
-    }
-  }
   static std::atomic<unsigned long long> lds_done{0};
-  if (int rc = reserve_lds(attn_fwd_kernel<DH, 1>, lds, lds_done, "attention_forward")) return rc;
-  hipLaunchKernelGGL((attn_fwd_kernel<DH, 1>), dim3((unsigned)(S / 128 * Hq * B)), dim3(256),
+  if (int rc = reserve_lds(attn_fwd_kernel<DH>, lds, lds_done, "attention_forward")) return rc;
+  const float scale_log2 = (float)(1.0 / sqrt((double)DH)) * kLog2e;
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((unsigned)(S / 128 * Hq * B)), dim3(256),
                      lds, st, (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse, (int)B, (int)S,
                      (int)Hq, (int)Hkv, scale_log2);
   return check_launch("attention_forward");
